@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched egocentric render on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+A step is one pass of the whole hot path over one batch of synthetic input that is already
+resident in device memory: world upload + occupancy packing + colour tables (mv_upload_worlds),
+camera records (mv_set_cameras, a fresh camera set every step) and the render
+(mv_render_batch) of every observation.  Prints ONE JSON line: observations/s (whole job), the
+roofline of the dominant kernel measured with HIP events around every render launch, and the CPU
+oracle timed on a bounded sample of the same workload on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E datasheet peak
+
+
+def algorithmic_bytes_per_obs(spec) -> float:
+    """HBM bytes the render of one observation must move: 7 bytes written per ray (3 colour +
+    4 depth), 1 material byte read per ray at the hit, the environment's occupancy bits and colour
+    table once per environment (shared by its A agents), one 64-byte camera record."""
+    X, Y, Z = spec.grid
+    rays = spec.width * spec.height
+    occ_bytes = ((X * Y * Z + 31) // 32) * 4
+    lut_bytes = 7 * (spec.num_materials + 1) * 4
+    return rays * 7 + rays * 1 + (occ_bytes + lut_bytes) / spec.agents_per_env + 64
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload index 1..4 (default 2: 4096 envs x 2 agents)")
+    ap.add_argument("--tiles-per-block", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-envs", type=int, default=4096)
+    ap.add_argument("--static-worlds", action="store_true",
+                    help="upload the worlds once instead of every step (not the headline number)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (environments are independent; "
+              "a second GPU would simply own other environments). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2107_08170_amd as mv
+    from paper_2107_08170_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    mv.load_library()
+
+    spec = synth.SPECS[args.config]
+    t0 = time.time()
+    wl = synth.generate(args.config)
+    gen_s = time.time() - t0
+    dev = torch.device("cuda", 0)
+    stream = torch.cuda.current_stream().cuda_stream
+    batch = mv.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height,
+                     tiles_per_block=args.tiles_per_block)
+    vox_d = torch.from_numpy(wl.voxels).to(dev)
+    pal_d = torch.from_numpy(wl.palette).to(dev)
+    n_sets = max(1, spec.steps)
+    if spec.dynamic:
+        # dynamic worlds: pre-compute the grids/cameras of a few steps on the host, keep them resident
+        n_sets = 4
+        grids, cams_l, self_l = [wl.voxels], [wl.cameras[0]], [wl.self_voxel[0]]
+        for _ in range(n_sets - 1):
+            g, c, s = synth.dynamic_step(wl)
+            grids.append(g); cams_l.append(c); self_l.append(s)
+        grids_d = [torch.from_numpy(g).to(dev) for g in grids]
+        cams_d = torch.from_numpy(np.stack(cams_l)).to(dev)
+        self_d = torch.from_numpy(np.stack(self_l)).to(dev)
+    else:
+        cams_np = wl.cameras
+        if cams_np.shape[0] < 8:
+            # single-pose workloads: re-draw view angles so that every timed step renders new cameras
+            rng = np.random.default_rng(synth.BASE_SEED + 100 + args.config)
+            n_sets = 8
+            cams_np = np.repeat(cams_np[:1], n_sets, axis=0).copy()
+            cams_np[1:, :, 3] = rng.uniform(0, 2 * np.pi, size=cams_np[1:, :, 3].shape)
+            cams_np[1:, :, 4] = rng.uniform(-np.pi / 6, np.pi / 6, size=cams_np[1:, :, 4].shape)
+        n_sets = cams_np.shape[0]
+        cams_d = torch.from_numpy(cams_np).to(dev)
+        grids_d, self_d = [vox_d], None
+
+    n, H, W = spec.num_obs, spec.height, spec.width
+    rgb = torch.empty((n, H, W, 3), dtype=torch.uint8, device=dev)
+    depth = torch.empty((n, H, W), dtype=torch.float32, device=dev)
+
+    def step(i, ev=None):
+        k = i % n_sets
+        if not args.static_worlds or i == 0:
+            batch.upload_worlds(grids_d[k % len(grids_d)], pal_d, stream=stream)
+        batch.set_cameras(cams_d[k], None if self_d is None else self_d[k], stream=stream)
+        if ev is not None:
+            ev[0].record()
+        batch.render(rgb, depth, stream=stream)
+        if ev is not None:
+            ev[1].record()
+
+    step(0)
+    for i in range(args.warmup):
+        step(i)
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    render_ms = np.array([a.elapsed_time(b) for a, b in events])
+    ms_per_step = elapsed * 1e3 / args.steps
+    obs_per_s = n * args.steps / elapsed
+    rays_per_obs = H * W
+    alg_bytes = algorithmic_bytes_per_obs(spec) * n
+    achieved = alg_bytes / (render_ms.mean() * 1e-3) / 1e9
+
+    result = {
+        "metric": "egocentric observations/sec (128x72 RGB+depth) on 1 MI355X",
+        "value": obs_per_s,
+        "unit": "observations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": spec.name, "num_envs": spec.num_envs, "agents_per_env": spec.agents_per_env,
+                   "grid": list(spec.grid), "image": [W, H], "num_materials": spec.num_materials,
+                   "observations_per_step": n, "camera_sets": int(n_sets),
+                   "step": ("render only after one upload" if args.static_worlds else
+                            "mv_upload_worlds(device) + mv_set_cameras(device) + mv_render_batch")},
+        "rays_per_s": obs_per_s * rays_per_obs,
+        "render_kernel_ms": {"mean": float(render_ms.mean()), "median": float(np.median(render_ms)),
+                             "p95": float(np.percentile(render_ms, 95))},
+        "render_only_obs_per_s": n / (render_ms.mean() * 1e-3),
+        "roofline": {"bound": "hbm", "kernel": "mv::render_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes},
+        "generator_seconds": gen_s,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        cores = min(os.cpu_count() or 1, 16)
+        envs = min(args.cpu_sample_envs, spec.num_envs)
+        ob = orc.OracleBatch(envs, spec.agents_per_env, spec.grid, W, H, spec.num_materials)
+        ob.upload_worlds(wl.voxels[:envs] if not spec.dynamic else grids[0][:envs], wl.palette[:envs])
+        first_cams = (cams_l[0] if spec.dynamic else cams_np[0])[: envs * spec.agents_per_env]
+        ob.set_cameras(first_cams, None if not spec.dynamic else self_l[0][: envs * spec.agents_per_env])
+        t0 = time.perf_counter()
+        ob.render(threads=cores, side_channels=False)
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": envs * spec.agents_per_env / cpu_s, "unit": "observations/s",
+                                  "cores": cores, "kind": "oracle",
+                                  "sample": f"first {envs} environments ({envs * spec.agents_per_env} observations) "
+                                            f"of camera set 0, {cpu_s:.2f} s wall"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

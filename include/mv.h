@@ -1,0 +1,146 @@
+/*
+ * mv.h -- C ABI of the batched egocentric voxel-world renderer for AMD MI355X (gfx950).
+ *
+ * One batch object holds N independent environments, each a voxel grid with one material id per
+ * voxel, and A agent cameras per environment (paper Sec. 3.2: one simulator instance hosts N
+ * environments with M agents each; here A = M).  One call renders the observation of every agent
+ * of every environment in a single GPU request (paper Sec. 3.2, Eq. 2: O = Render(S)), as an
+ * [N*A, H, W, 3] uint8 colour tensor (paper App. A.2: 128x72 RGB observations) plus an
+ * [N*A, H, W] float32 depth tensor, both left in device memory (paper Sec. 3.2, last paragraph:
+ * observations may stay on the GPU).  Observation index = env * A + agent (paper App. A.1: a
+ * vector of N x M observations).
+ *
+ * What a pixel holds (the paper rasterises and gives no formula; this is the stated reading):
+ * the ray from the camera position through the pixel centre of a pinhole camera (yaw about +z
+ * measured from +x, pitch positive upwards, no roll, horizontal field of view hfov, square
+ * pixels, row 0 at the top, column 0 at the left) is followed voxel by voxel (3D DDA) to the
+ * first solid voxel (material id != 0) that is not part of the camera's own body.  Colour is that
+ * voxel's palette colour (paper Sec. 4: flat "monochrome" materials, re-drawn per episode, hence
+ * one palette per environment) times ambient + diffuse * max(0, n.L) for the face the ray entered
+ * through, rounded to nearest; depth is the planar distance along the camera's forward axis in
+ * voxel units.  Rays that leave the grid get sky_rgb and depth 0.
+ *
+ * Coordinates: voxel (i,j,k) is the cube [i,i+1) x [j,j+1) x [k,k+1), z is up, unit voxels.
+ * Grids are stored x fastest: linear voxel index = (k*Y + j)*X + i.
+ *
+ * All entry points return MV_OK (0) or a negative mv_status; none throws, aborts or prints.
+ * mv_last_error() returns a thread-local, NUL-terminated description of the last failure on
+ * the calling thread.  Work is enqueued on the caller's HIP stream and the calls return without
+ * synchronising; ordering between calls is stream order.  A batch must not be used from two
+ * threads at once.
+ */
+#ifndef MV_H
+#define MV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MV_OK           =  0,
+    MV_ERR_ARG      = -1,   /* null pointer, non-positive size, non-finite camera (host data)      */
+    MV_ERR_STATE    = -2,   /* render before every environment and the cameras have been supplied  */
+    MV_ERR_RANGE    = -3,   /* environment range outside the batch, material id > num_materials    */
+    MV_ERR_CAPACITY = -4,   /* grid + image tile do not fit the per-workgroup LDS plan             */
+    MV_ERR_HIP      = -5    /* a HIP runtime call failed; text in mv_last_error()                  */
+} mv_status;
+
+/* Face codes written to aux_face: outward normal of the voxel face the ray entered through. */
+#define MV_FACE_NEG_X   0
+#define MV_FACE_POS_X   1
+#define MV_FACE_NEG_Y   2
+#define MV_FACE_POS_Y   3
+#define MV_FACE_NEG_Z   4
+#define MV_FACE_POS_Z   5
+#define MV_FACE_INSIDE  6     /* camera position is inside a solid voxel: depth 0, ambient only */
+#define MV_FACE_MISS    255
+
+typedef struct mv_batch mv_batch;     /* opaque; created and destroyed by the library */
+
+typedef struct {
+    int32_t num_envs;          /* N >= 1                                                          */
+    int32_t agents_per_env;    /* A >= 1                                                          */
+    int32_t grid_x, grid_y, grid_z;   /* voxels per axis, each >= 1                               */
+    int32_t width, height;     /* image size in pixels, each >= 1 (128x72 in the paper)           */
+    float   hfov_rad;          /* horizontal field of view, 0 < hfov < pi                         */
+    int32_t num_materials;     /* 1..255; id 0 means empty                                        */
+    float   light_dir[3];      /* direction TOWARDS the light, any non-zero length                */
+    float   ambient, diffuse;  /* face intensity = ambient + diffuse * max(0, n.L)                */
+    uint8_t sky_rgb[3];        /* colour of rays that leave the grid                              */
+    uint8_t reserved0;         /* must be 0                                                       */
+    int32_t device;            /* HIP device ordinal                                              */
+    int32_t tiles_per_block;   /* 0 = choose automatically; otherwise the number of 8x8-pixel
+                                  tiles one workgroup renders (a launch-shape knob, results do
+                                  not depend on it)                                               */
+} mv_config;
+
+/* Fill *cfg with the defaults used throughout the paper-shaped workloads: 128x72 pixels, hfov
+ * pi/2, light towards (1,2,3), ambient 0.30, diffuse 0.70, sky (135,206,235), device 0; the
+ * sizes (num_envs, agents_per_env, grid, num_materials) are set to 0 and must be filled in. */
+void mv_default_config(mv_config* cfg);
+
+/* Create a batch on cfg->device (paper Sec. 3.2: N environments x M agents per instance).
+ * Allocates all device memory the batch will ever use: material grids N*X*Y*Z bytes,
+ * occupancy bits, per-environment shaded colour tables, camera records.  *out is written only
+ * on success.  Errors: MV_ERR_ARG (bad field), MV_ERR_CAPACITY (the occupancy bits of one
+ * grid do not fit in LDS), MV_ERR_HIP. */
+int mv_create_batch(const mv_config* cfg, mv_batch** out);
+
+/* Replace the voxel grids of environments first_env .. first_env+count-1 (paper Sec. 3.1: the
+ * world is a voxel grid; Sec. 4: layouts and materials are randomised per episode).
+ *   voxels  : [count, Z, Y, X] uint8 material ids, x fastest.  Host memory if src_is_device == 0,
+ *             device memory on the batch's device otherwise.  Copied; the caller keeps ownership
+ *             and may reuse the buffer once the stream has passed this call (host memory: on
+ *             return).
+ *   palette : [count, num_materials+1, 3] uint8 RGB, row 0 ignored; same memory space as voxels;
+ *             NULL keeps the palettes already uploaded.
+ * Packs occupancy bits and re-shades the colour tables on `stream`.  Host data is validated
+ * (material id > num_materials -> MV_ERR_RANGE, nothing is changed); device data is not, ids
+ * above num_materials are clamped to num_materials when shading.
+ * Errors: MV_ERR_ARG, MV_ERR_RANGE, MV_ERR_HIP. */
+int mv_upload_worlds(mv_batch* batch, int32_t first_env, int32_t count, const uint8_t* voxels,
+                     const uint8_t* palette, int32_t src_is_device, void* hip_stream);
+
+/* Set all N*A cameras (paper Sec. 3.2: cameras are entities of the state S that Render reads).
+ *   cams       : [N*A, 5] float32 rows (x, y, z, yaw, pitch), observation order env*A+agent.
+ *   self_voxel : [N*A] int32, linear index of the LOWER voxel of the camera's own 1x1x2 body
+ *                (that voxel and the one directly above are invisible to this camera only), or
+ *                -1 for none; NULL means -1 everywhere.
+ * Host memory if src_is_device == 0 (validated: non-finite value -> MV_ERR_ARG), else device
+ * memory (not validated).  The camera basis is computed on the GPU in float64 and rounded to
+ * float32 records on `stream`.  Errors: MV_ERR_ARG, MV_ERR_HIP. */
+int mv_set_cameras(mv_batch* batch, const float* cams, const int32_t* self_voxel,
+                   int32_t src_is_device, void* hip_stream);
+
+/* Render every observation (paper Sec. 3.2, Eq. 2) into caller-owned DEVICE memory:
+ *   rgb           : [N*A, H, W, 3] uint8, required.
+ *   depth         : [N*A, H, W] float32, required; 0.0f where the ray leaves the grid.
+ *   aux_material  : [N*A, H, W] uint8 material id of the hit voxel (0 on a miss), or NULL.
+ *   aux_hit_index : [N*A, H, W] int32 linear index of the hit voxel (-1 on a miss), or NULL.
+ *   aux_face      : [N*A, H, W] uint8 MV_FACE_* code, or NULL.
+ * One kernel launch on `stream`; returns without synchronising.
+ * Errors: MV_ERR_ARG, MV_ERR_STATE (some environment or the cameras never supplied), MV_ERR_HIP. */
+int mv_render_batch(mv_batch* batch, uint8_t* rgb, float* depth, uint8_t* aux_material,
+                    int32_t* aux_hit_index, uint8_t* aux_face, void* hip_stream);
+
+/* Free the batch and its device memory (synchronises the device first).  NULL is a no-op. */
+void mv_destroy(mv_batch* batch);
+
+/* Description of the last error on this thread ("" if none).  Never NULL. */
+const char* mv_last_error(void);
+
+/* Introspection for tests and benchmarks (device pointers stay owned by the batch):
+ *   mv_debug_occupancy : device pointer to the packed occupancy words of environment `env`
+ *                        and the number of 32-bit words per environment; bit b of word w is
+ *                        voxel 32*w + b.
+ *   mv_debug_camera_records : device pointer to the [N*A] 64-byte camera records
+ *                        (float P[3], F[3], R[3], U[3]; int32 self_lo, self_hi; 8 bytes pad). */
+int mv_debug_occupancy(mv_batch* batch, int32_t env, const uint32_t** words, int32_t* words_per_env);
+int mv_debug_camera_records(mv_batch* batch, const void** records);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,169 @@
+"""ctypes binding of ``libmv.so``: the same five calls as ``include/mv.h``, argument marshalling only.
+
+Every step of the render path runs in the HIP kernels behind the C ABI; there is no Python or CPU
+fallback.  If the library has not been built, loading fails with an error that says how to build
+it.  PyTorch is used by callers only to own device memory and streams: tensors are passed here as
+raw device pointers (``tensor.data_ptr()``) and the stream as ``torch.cuda.current_stream().cuda_stream``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libmv.so")
+
+MV_OK, MV_ERR_ARG, MV_ERR_STATE, MV_ERR_RANGE, MV_ERR_CAPACITY, MV_ERR_HIP = 0, -1, -2, -3, -4, -5
+FACE_INSIDE, FACE_MISS = 6, 255
+
+EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_set_cameras",
+           "mv_render_batch", "mv_destroy", "mv_last_error", "mv_debug_occupancy",
+           "mv_debug_camera_records")
+
+
+class MvConfig(C.Structure):
+    """Mirror of ``mv_config``."""
+    _fields_ = [("num_envs", C.c_int32), ("agents_per_env", C.c_int32),
+                ("grid_x", C.c_int32), ("grid_y", C.c_int32), ("grid_z", C.c_int32),
+                ("width", C.c_int32), ("height", C.c_int32), ("hfov_rad", C.c_float),
+                ("num_materials", C.c_int32), ("light_dir", C.c_float * 3),
+                ("ambient", C.c_float), ("diffuse", C.c_float), ("sky_rgb", C.c_uint8 * 3),
+                ("reserved0", C.c_uint8), ("device", C.c_int32), ("tiles_per_block", C.c_int32)]
+
+
+class MvError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"mv error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load ``libmv.so`` (built by ``python -m paper_2107_08170_amd.build``); fails loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2107_08170_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp = C.c_void_p
+    lib.mv_default_config.argtypes = [C.POINTER(MvConfig)]
+    lib.mv_default_config.restype = None
+    lib.mv_create_batch.argtypes = [C.POINTER(MvConfig), C.POINTER(vp)]
+    lib.mv_upload_worlds.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp]
+    lib.mv_set_cameras.argtypes = [vp, vp, vp, C.c_int32, vp]
+    lib.mv_render_batch.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.mv_destroy.argtypes = [vp]
+    lib.mv_destroy.restype = None
+    lib.mv_last_error.restype = C.c_char_p
+    lib.mv_debug_occupancy.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_int32)]
+    lib.mv_debug_camera_records.argtypes = [vp, C.POINTER(vp)]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != MV_OK:
+        raise MvError(rc, load_library().mv_last_error().decode("utf-8", "replace"))
+
+
+def default_config() -> MvConfig:
+    cfg = MvConfig()
+    load_library().mv_default_config(C.byref(cfg))
+    return cfg
+
+
+def _as_ptr(x) -> Optional[int]:
+    """Raw address of a torch tensor, a NumPy array, an int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):
+        return x.ctypes.data
+    raise TypeError(f"cannot take the address of {type(x)!r}")
+
+
+def _is_device(x) -> bool:
+    return bool(getattr(x, "is_cuda", False))
+
+
+class Batch:
+    """N environments x A agent cameras on one GPU (thin wrapper over the ``mv_batch*`` handle)."""
+
+    def __init__(self, num_envs: int, agents_per_env: int, grid: Sequence[int], num_materials: int,
+                 width: int = 128, height: int = 72, hfov_rad: Optional[float] = None,
+                 light_dir: Optional[Sequence[float]] = None, ambient: Optional[float] = None,
+                 diffuse: Optional[float] = None, sky_rgb: Optional[Sequence[int]] = None,
+                 device: int = 0, tiles_per_block: int = 0):
+        lib = load_library()
+        cfg = default_config()
+        cfg.num_envs, cfg.agents_per_env = num_envs, agents_per_env
+        cfg.grid_x, cfg.grid_y, cfg.grid_z = (int(g) for g in grid)
+        cfg.width, cfg.height = width, height
+        cfg.num_materials = num_materials
+        if hfov_rad is not None:
+            cfg.hfov_rad = hfov_rad
+        if light_dir is not None:
+            cfg.light_dir[:] = [float(v) for v in light_dir]
+        if ambient is not None:
+            cfg.ambient = ambient
+        if diffuse is not None:
+            cfg.diffuse = diffuse
+        if sky_rgb is not None:
+            cfg.sky_rgb[:] = [int(v) for v in sky_rgb]
+        cfg.device = device
+        cfg.tiles_per_block = tiles_per_block
+        self.cfg = cfg
+        self._h = C.c_void_p()
+        _check(lib.mv_create_batch(C.byref(cfg), C.byref(self._h)))
+        self.num_obs = num_envs * agents_per_env
+
+    def upload_worlds(self, voxels, palette=None, first_env: int = 0, count: Optional[int] = None,
+                      stream: int = 0) -> None:
+        """``voxels`` u8[count,Z,Y,X] and ``palette`` u8[count,M+1,3]: both torch CUDA tensors or both
+        host arrays (NumPy / CPU tensors)."""
+        if count is None:
+            count = int(voxels.shape[0])
+        dev = _is_device(voxels)
+        if palette is not None and _is_device(palette) != dev:
+            raise ValueError("voxels and palette must live in the same memory space")
+        _check(load_library().mv_upload_worlds(self._h, first_env, count, _as_ptr(voxels), _as_ptr(palette),
+                                               1 if dev else 0, stream))
+
+    def set_cameras(self, cams, self_voxel=None, stream: int = 0) -> None:
+        dev = _is_device(cams)
+        if self_voxel is not None and _is_device(self_voxel) != dev:
+            raise ValueError("cams and self_voxel must live in the same memory space")
+        _check(load_library().mv_set_cameras(self._h, _as_ptr(cams), _as_ptr(self_voxel), 1 if dev else 0, stream))
+
+    def render(self, rgb, depth, aux_material=None, aux_hit_index=None, aux_face=None, stream: int = 0) -> None:
+        _check(load_library().mv_render_batch(self._h, _as_ptr(rgb), _as_ptr(depth), _as_ptr(aux_material),
+                                              _as_ptr(aux_hit_index), _as_ptr(aux_face), stream))
+
+    def debug_occupancy(self, env: int):
+        ptr, n = C.c_void_p(), C.c_int32()
+        _check(load_library().mv_debug_occupancy(self._h, env, C.byref(ptr), C.byref(n)))
+        return ptr.value, n.value
+
+    def debug_camera_records(self) -> int:
+        ptr = C.c_void_p()
+        _check(load_library().mv_debug_camera_records(self._h, C.byref(ptr)))
+        return ptr.value
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            load_library().mv_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

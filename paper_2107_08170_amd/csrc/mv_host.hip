@@ -1,0 +1,339 @@
+// Host runtime of the batched voxel-world renderer: the batch object, argument checking, device
+// memory, and the C ABI declared in include/mv.h.  Every arithmetic step of the render path runs
+// in the kernels of mv_kernels.hip; this file only validates, allocates, copies and launches.
+#include "mv.h"
+#include "mv_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define MV_HIP(expr)                                                                                  \
+    do {                                                                                              \
+        hipError_t e_ = (expr);                                                                       \
+        if (e_ != hipSuccess)                                                                         \
+            return fail(MV_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+// Makes the batch's device current for the duration of a call and restores the caller's.
+class DeviceScope {
+public:
+    explicit DeviceScope(int device) : ok_(false), prev_(-1)
+    {
+        if (hipGetDevice(&prev_) != hipSuccess) return;
+        if (prev_ != device && hipSetDevice(device) != hipSuccess) return;
+        ok_ = true;
+        target_ = device;
+    }
+    ~DeviceScope()
+    {
+        if (ok_ && prev_ != target_) (void)hipSetDevice(prev_);
+    }
+    bool ok() const { return ok_; }
+
+private:
+    bool ok_;
+    int prev_, target_ = -1;
+};
+
+constexpr size_t kLdsBudget = 64 * 1024;      // per-workgroup LDS the render kernel may ask for
+
+}  // namespace
+
+struct mv_batch {
+    mv_config cfg{};
+    int num_obs = 0;
+    int voxels_per_env = 0;
+    int words_per_env = 0;
+    int materials_plus_one = 0;
+    double tan_half_x = 0, tan_half_y = 0;
+    float intensity[mv::kNumFaces] = {};
+    size_t lds_bytes = 0;
+
+    uint8_t* d_vox = nullptr;
+    uint32_t* d_occ = nullptr;
+    uint8_t* d_palette = nullptr;
+    uint32_t* d_lut = nullptr;
+    float* d_sx = nullptr;
+    float* d_sy = nullptr;
+    float* d_cams = nullptr;          // staging for host-supplied cameras
+    int32_t* d_self = nullptr;
+    mv::CameraRecord* d_rec = nullptr;
+
+    std::vector<uint8_t> env_has_grid, env_has_palette;
+    int envs_with_grid = 0, envs_with_palette = 0;
+    bool cameras_set = false;
+};
+
+static void free_batch(mv_batch* b)
+{
+    if (!b) return;
+    (void)hipFree(b->d_vox); (void)hipFree(b->d_occ); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
+    (void)hipFree(b->d_sx); (void)hipFree(b->d_sy); (void)hipFree(b->d_cams); (void)hipFree(b->d_self);
+    (void)hipFree(b->d_rec);
+    delete b;
+}
+
+extern "C" {
+
+const char* mv_last_error(void) { return g_error; }
+
+void mv_default_config(mv_config* cfg)
+{
+    if (!cfg) return;
+    std::memset(cfg, 0, sizeof(*cfg));
+    cfg->width = 128;
+    cfg->height = 72;
+    cfg->hfov_rad = 1.57079637f;
+    cfg->light_dir[0] = 1.0f; cfg->light_dir[1] = 2.0f; cfg->light_dir[2] = 3.0f;
+    cfg->ambient = 0.30f;
+    cfg->diffuse = 0.70f;
+    cfg->sky_rgb[0] = 135; cfg->sky_rgb[1] = 206; cfg->sky_rgb[2] = 235;
+}
+
+int mv_create_batch(const mv_config* cfg, mv_batch** out)
+{
+    if (!cfg || !out) return fail(MV_ERR_ARG, "mv_create_batch: null argument");
+    if (cfg->num_envs <= 0 || cfg->agents_per_env <= 0)
+        return fail(MV_ERR_ARG, "mv_create_batch: num_envs and agents_per_env must be positive");
+    if (cfg->grid_x <= 0 || cfg->grid_y <= 0 || cfg->grid_z <= 0)
+        return fail(MV_ERR_ARG, "mv_create_batch: grid dimensions must be positive");
+    if (cfg->width <= 0 || cfg->height <= 0 || cfg->width > 16384 || cfg->height > 16384)
+        return fail(MV_ERR_ARG, "mv_create_batch: image size must be in 1..16384");
+    if (!(cfg->hfov_rad > 0.0f) || !(cfg->hfov_rad < 3.14159f))
+        return fail(MV_ERR_ARG, "mv_create_batch: hfov_rad must lie in (0, pi)");
+    if (cfg->num_materials < 1 || cfg->num_materials > 255)
+        return fail(MV_ERR_ARG, "mv_create_batch: num_materials must be in 1..255");
+    if (cfg->reserved0 != 0) return fail(MV_ERR_ARG, "mv_create_batch: reserved0 must be 0");
+    if (cfg->tiles_per_block < 0) return fail(MV_ERR_ARG, "mv_create_batch: tiles_per_block must be >= 0");
+    if (cfg->device < 0) return fail(MV_ERR_ARG, "mv_create_batch: device must be >= 0");
+    const double lx = cfg->light_dir[0], ly = cfg->light_dir[1], lz = cfg->light_dir[2];
+    const double ln = std::sqrt(lx * lx + ly * ly + lz * lz);
+    if (!(ln > 0.0) || !std::isfinite(ln)) return fail(MV_ERR_ARG, "mv_create_batch: light_dir must be finite and non-zero");
+    if (!std::isfinite(cfg->ambient) || !std::isfinite(cfg->diffuse))
+        return fail(MV_ERR_ARG, "mv_create_batch: ambient/diffuse must be finite");
+
+    const long long voxels = (long long)cfg->grid_x * cfg->grid_y * cfg->grid_z;
+    if (voxels > (1ll << 30)) return fail(MV_ERR_CAPACITY, "mv_create_batch: grid too large");
+    const long long num_obs = (long long)cfg->num_envs * cfg->agents_per_env;
+    if (num_obs > (1ll << 24)) return fail(MV_ERR_ARG, "mv_create_batch: more than 2^24 observations");
+    const int words = (int)((voxels + 31) / 32);
+    const size_t lds = mv::render_lds_bytes(words);
+    if (lds > kLdsBudget)
+        return fail(MV_ERR_CAPACITY, "mv_create_batch: occupancy bits of one grid need %zu bytes of LDS, budget is %zu",
+                    lds, kLdsBudget);
+
+    int device_count = 0;
+    MV_HIP(hipGetDeviceCount(&device_count));
+    if (cfg->device >= device_count) return fail(MV_ERR_ARG, "mv_create_batch: device %d of %d", cfg->device, device_count);
+    DeviceScope scope(cfg->device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_create_batch: cannot select device %d", cfg->device);
+
+    mv_batch* b = new (std::nothrow) mv_batch;
+    if (!b) return fail(MV_ERR_HIP, "mv_create_batch: out of host memory");
+    b->cfg = *cfg;
+    b->num_obs = (int)num_obs;
+    b->voxels_per_env = (int)voxels;
+    b->words_per_env = words;
+    b->materials_plus_one = cfg->num_materials + 1;
+    b->lds_bytes = lds;
+    b->tan_half_x = std::tan(0.5 * (double)cfg->hfov_rad);
+    b->tan_half_y = b->tan_half_x * (double)cfg->height / (double)cfg->width;
+    // Face intensities are batch constants: ambient + diffuse * max(0, n.L) for the six axis
+    // normals (0:-x 1:+x 2:-y 3:+y 4:-z 5:+z), ambient alone for "inside".
+    const double L[3] = { lx / ln, ly / ln, lz / ln };
+    for (int f = 0; f < 6; ++f) {
+        double ndotl = (f & 1) ? L[f >> 1] : -L[f >> 1];
+        if (ndotl < 0.0) ndotl = 0.0;
+        b->intensity[f] = (float)((double)cfg->ambient + (double)cfg->diffuse * ndotl);
+    }
+    b->intensity[6] = cfg->ambient;
+    b->env_has_grid.assign((size_t)cfg->num_envs, 0);
+    b->env_has_palette.assign((size_t)cfg->num_envs, 0);
+
+    const size_t N = (size_t)cfg->num_envs;
+    hipError_t e = hipSuccess;
+    auto alloc = [&](void** p, size_t bytes) {
+        if (e == hipSuccess) e = hipMalloc(p, bytes);
+    };
+    alloc((void**)&b->d_vox, N * (size_t)voxels);
+    alloc((void**)&b->d_occ, N * (size_t)words * 4);
+    alloc((void**)&b->d_palette, N * (size_t)b->materials_plus_one * 3);
+    alloc((void**)&b->d_lut, N * (size_t)mv::kNumFaces * b->materials_plus_one * 4);
+    alloc((void**)&b->d_sx, (size_t)cfg->width * 4);
+    alloc((void**)&b->d_sy, (size_t)cfg->height * 4);
+    alloc((void**)&b->d_cams, (size_t)num_obs * 5 * 4);
+    alloc((void**)&b->d_self, (size_t)num_obs * 4);
+    alloc((void**)&b->d_rec, (size_t)num_obs * sizeof(mv::CameraRecord));
+    if (e == hipSuccess) e = mv::launch_pixel_scalars(b->d_sx, b->d_sy, cfg->width, cfg->height, nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) {
+        free_batch(b);
+        return fail(MV_ERR_HIP, "mv_create_batch: device set-up failed: %s", hipGetErrorString(e));
+    }
+    *out = b;
+    return MV_OK;
+}
+
+int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_t* voxels, const uint8_t* palette,
+                     int32_t src_is_device, void* hip_stream)
+{
+    if (!b || !voxels) return fail(MV_ERR_ARG, "mv_upload_worlds: null argument");
+    if (count <= 0) return fail(MV_ERR_ARG, "mv_upload_worlds: count must be positive");
+    if (first_env < 0 || first_env > b->cfg.num_envs - count)
+        return fail(MV_ERR_RANGE, "mv_upload_worlds: environments %d..%d outside 0..%d", first_env,
+                    first_env + count - 1, b->cfg.num_envs - 1);
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_upload_worlds: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t V = (size_t)b->voxels_per_env;
+    const size_t pal_bytes = (size_t)b->materials_plus_one * 3;
+    uint8_t* vox_dst = b->d_vox + (size_t)first_env * V;
+    uint8_t* pal_dst = b->d_palette + (size_t)first_env * pal_bytes;
+    uint32_t* occ_dst = b->d_occ + (size_t)first_env * b->words_per_env;
+    uint32_t* lut_dst = b->d_lut + (size_t)first_env * mv::kNumFaces * b->materials_plus_one;
+
+    if (!src_is_device) {
+        const size_t n = (size_t)count * V;
+        const uint8_t limit = (uint8_t)b->cfg.num_materials;
+        for (size_t i = 0; i < n; ++i)
+            if (voxels[i] > limit)
+                return fail(MV_ERR_RANGE, "mv_upload_worlds: material id %d at voxel %zu exceeds num_materials %d",
+                            (int)voxels[i], i, (int)limit);
+        MV_HIP(hipMemcpyAsync(vox_dst, voxels, n, hipMemcpyHostToDevice, stream));
+        if (palette) MV_HIP(hipMemcpyAsync(pal_dst, palette, (size_t)count * pal_bytes, hipMemcpyHostToDevice, stream));
+        // pageable host memory: make sure the runtime is done reading it before we return
+        MV_HIP(hipStreamSynchronize(stream));
+        MV_HIP(mv::launch_pack(vox_dst, vox_dst, occ_dst, count, b->voxels_per_env, b->words_per_env, stream));
+    } else {
+        if (palette)
+            MV_HIP(hipMemcpyAsync(pal_dst, palette, (size_t)count * pal_bytes, hipMemcpyDeviceToDevice, stream));
+        MV_HIP(mv::launch_pack(voxels, vox_dst, occ_dst, count, b->voxels_per_env, b->words_per_env, stream));
+    }
+    if (palette)
+        MV_HIP(mv::launch_shade_tables(pal_dst, lut_dst, count, b->materials_plus_one, b->intensity, stream));
+
+    for (int e = first_env; e < first_env + count; ++e) {
+        if (!b->env_has_grid[e]) { b->env_has_grid[e] = 1; ++b->envs_with_grid; }
+        if (palette && !b->env_has_palette[e]) { b->env_has_palette[e] = 1; ++b->envs_with_palette; }
+    }
+    return MV_OK;
+}
+
+int mv_set_cameras(mv_batch* b, const float* cams, const int32_t* self_voxel, int32_t src_is_device, void* hip_stream)
+{
+    if (!b || !cams) return fail(MV_ERR_ARG, "mv_set_cameras: null argument");
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_set_cameras: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const float* d_cams = cams;
+    const int32_t* d_self = self_voxel;
+    if (!src_is_device) {
+        const size_t n = (size_t)b->num_obs * 5;
+        for (size_t i = 0; i < n; ++i)
+            if (!std::isfinite(cams[i])) return fail(MV_ERR_ARG, "mv_set_cameras: non-finite value at float %zu", i);
+        if (self_voxel)
+            for (int o = 0; o < b->num_obs; ++o)
+                if (self_voxel[o] < -1 || self_voxel[o] >= b->voxels_per_env)
+                    return fail(MV_ERR_RANGE, "mv_set_cameras: self_voxel[%d] = %d outside the grid", o, self_voxel[o]);
+        MV_HIP(hipMemcpyAsync(b->d_cams, cams, n * 4, hipMemcpyHostToDevice, stream));
+        if (self_voxel) MV_HIP(hipMemcpyAsync(b->d_self, self_voxel, (size_t)b->num_obs * 4, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipStreamSynchronize(stream));
+        d_cams = b->d_cams;
+        d_self = self_voxel ? b->d_self : nullptr;
+    }
+    MV_HIP(mv::launch_cameras(d_cams, d_self, b->d_rec, b->num_obs, b->tan_half_x, b->tan_half_y,
+                              b->cfg.grid_x * b->cfg.grid_y, stream));
+    b->cameras_set = true;
+    return MV_OK;
+}
+
+int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_material, int32_t* aux_hit_index,
+                    uint8_t* aux_face, void* hip_stream)
+{
+    if (!b || !rgb || !depth) return fail(MV_ERR_ARG, "mv_render_batch: null argument");
+    if ((reinterpret_cast<uintptr_t>(depth) & 3) || (aux_hit_index && (reinterpret_cast<uintptr_t>(aux_hit_index) & 3)))
+        return fail(MV_ERR_ARG, "mv_render_batch: depth and aux_hit_index must be 4-byte aligned");
+    if (b->envs_with_grid != b->cfg.num_envs || b->envs_with_palette != b->cfg.num_envs)
+        return fail(MV_ERR_STATE, "mv_render_batch: %d of %d environments have a grid, %d a palette", b->envs_with_grid,
+                    b->cfg.num_envs, b->envs_with_palette);
+    if (!b->cameras_set) return fail(MV_ERR_STATE, "mv_render_batch: cameras were never set");
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_render_batch: cannot select device %d", b->cfg.device);
+
+    mv::RenderParams p{};
+    p.occ = b->d_occ; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
+    p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
+    p.words_per_env = b->words_per_env;
+    p.voxels_per_env = b->voxels_per_env;
+    p.X = b->cfg.grid_x; p.Y = b->cfg.grid_y; p.Z = b->cfg.grid_z;
+    p.W = b->cfg.width; p.H = b->cfg.height; p.A = b->cfg.agents_per_env;
+    p.materials_plus_one = b->materials_plus_one;
+    p.tiles_x = (p.W + mv::kTile - 1) / mv::kTile;
+    const int tiles_y = (p.H + mv::kTile - 1) / mv::kTile;
+    p.tiles_per_obs = p.tiles_x * tiles_y;
+    int tpb = b->cfg.tiles_per_block;
+    if (tpb <= 0) {
+        // Enough workgroups to fill 256 CUs several times over, but no more re-staging of the
+        // grid than needed: whole observations per block for large batches, strips otherwise.
+        const long long target_blocks = 256ll * 32;
+        long long per_obs = (target_blocks + b->num_obs - 1) / b->num_obs;
+        if (per_obs < 1) per_obs = 1;
+        tpb = (int)((p.tiles_per_obs + per_obs - 1) / per_obs);
+        const int min_tpb = mv::kWavesPerBlock * 2;
+        if (tpb < min_tpb) tpb = min_tpb;
+    }
+    if (tpb > p.tiles_per_obs) tpb = p.tiles_per_obs;
+    p.tiles_per_block = tpb;
+    p.blocks_per_obs = (p.tiles_per_obs + tpb - 1) / tpb;
+    const unsigned long long total = (unsigned long long)p.blocks_per_obs * (unsigned long long)b->num_obs;
+    if (total > 0x7fffffffull - mv::kXcds) return fail(MV_ERR_CAPACITY, "mv_render_batch: too many workgroups");
+    p.total_blocks = (uint32_t)total;
+    p.blocks_per_xcd = (uint32_t)((total + mv::kXcds - 1) / mv::kXcds);
+    p.sky_packed = (uint32_t)b->cfg.sky_rgb[0] | ((uint32_t)b->cfg.sky_rgb[1] << 8) | ((uint32_t)b->cfg.sky_rgb[2] << 16);
+    p.max_steps = p.X + p.Y + p.Z + 3;
+    MV_HIP(mv::launch_render(p, b->lds_bytes, (hipStream_t)hip_stream));
+    return MV_OK;
+}
+
+void mv_destroy(mv_batch* b)
+{
+    if (!b) return;
+    DeviceScope scope(b->cfg.device);
+    if (scope.ok()) (void)hipDeviceSynchronize();
+    free_batch(b);
+}
+
+int mv_debug_occupancy(mv_batch* b, int32_t env, const uint32_t** words, int32_t* words_per_env)
+{
+    if (!b || !words || !words_per_env) return fail(MV_ERR_ARG, "mv_debug_occupancy: null argument");
+    if (env < 0 || env >= b->cfg.num_envs) return fail(MV_ERR_RANGE, "mv_debug_occupancy: env %d", env);
+    *words = b->d_occ + (size_t)env * b->words_per_env;
+    *words_per_env = b->words_per_env;
+    return MV_OK;
+}
+
+int mv_debug_camera_records(mv_batch* b, const void** records)
+{
+    if (!b || !records) return fail(MV_ERR_ARG, "mv_debug_camera_records: null argument");
+    *records = b->d_rec;
+    return MV_OK;
+}
+
+}  // extern "C"
