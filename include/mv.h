@@ -84,8 +84,9 @@ void mv_default_config(mv_config* cfg);
 /* Create a batch on cfg->device (paper Sec. 3.2: N environments x M agents per instance).
  * Allocates all device memory the batch will ever use: material grids N*X*Y*Z bytes,
  * occupancy bits, per-environment shaded colour tables, camera records.  *out is written only
- * on success.  Errors: MV_ERR_ARG (bad field), MV_ERR_CAPACITY (the occupancy bits of one
- * grid do not fit in LDS), MV_ERR_HIP. */
+ * on success.  Grids up to 64x64 voxels in x and y take the fast row-scan traversal; wider grids
+ * are rendered with a plain per-cell DDA.  Errors: MV_ERR_ARG (bad field), MV_ERR_CAPACITY (the
+ * occupancy bits of one grid do not fit in the 160 KiB of LDS of a compute unit), MV_ERR_HIP. */
 int mv_create_batch(const mv_config* cfg, mv_batch** out);
 
 /* Replace the voxel grids of environments first_env .. first_env+count-1 (paper Sec. 3.1: the
@@ -132,12 +133,15 @@ void mv_destroy(mv_batch* batch);
 const char* mv_last_error(void);
 
 /* Introspection for tests and benchmarks (device pointers stay owned by the batch):
- *   mv_debug_occupancy : device pointer to the packed occupancy words of environment `env`
- *                        and the number of 32-bit words per environment; bit b of word w is
- *                        voxel 32*w + b.
+ *   mv_debug_occupancy : device pointers to the packed occupancy "bit rows" of environment `env`.
+ *                        x rows: Z*Y rows of *x_row_words 64-bit words, row k*Y+j, bit i of the row
+ *                        is voxel (i,j,k); y rows: Z*X rows of *y_row_words words, row k*X+i, bit j
+ *                        is voxel (i,j,k); *top_layer points to one int32: 1 + the highest layer k
+ *                        that holds a solid voxel (0 for an empty grid).
  *   mv_debug_camera_records : device pointer to the [N*A] 64-byte camera records
  *                        (float P[3], F[3], R[3], U[3]; int32 self_lo, self_hi; 8 bytes pad). */
-int mv_debug_occupancy(mv_batch* batch, int32_t env, const uint32_t** words, int32_t* words_per_env);
+int mv_debug_occupancy(mv_batch* batch, int32_t env, const uint64_t** x_rows, int32_t* x_row_words,
+                       const uint64_t** y_rows, int32_t* y_row_words, const int32_t** top_layer);
 int mv_debug_camera_records(mv_batch* batch, const void** records);
 
 #ifdef __cplusplus

@@ -60,7 +60,8 @@ def load_library():
     lib.mv_destroy.argtypes = [vp]
     lib.mv_destroy.restype = None
     lib.mv_last_error.restype = C.c_char_p
-    lib.mv_debug_occupancy.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_int32)]
+    lib.mv_debug_occupancy.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_int32), C.POINTER(vp),
+                                       C.POINTER(C.c_int32), C.POINTER(vp)]
     lib.mv_debug_camera_records.argtypes = [vp, C.POINTER(vp)]
     _lib = lib
     return lib
@@ -148,9 +149,12 @@ class Batch:
                                               _as_ptr(aux_hit_index), _as_ptr(aux_face), stream))
 
     def debug_occupancy(self, env: int):
-        ptr, n = C.c_void_p(), C.c_int32()
-        _check(load_library().mv_debug_occupancy(self._h, env, C.byref(ptr), C.byref(n)))
-        return ptr.value, n.value
+        """(x_rows_ptr, x_row_words, y_rows_ptr, y_row_words, top_layer_ptr) of one environment."""
+        xp, yp, tp = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        xw, yw = C.c_int32(), C.c_int32()
+        _check(load_library().mv_debug_occupancy(self._h, env, C.byref(xp), C.byref(xw), C.byref(yp), C.byref(yw),
+                                                 C.byref(tp)))
+        return xp.value, xw.value, yp.value, yw.value, tp.value
 
     def debug_camera_records(self) -> int:
         ptr = C.c_void_p()

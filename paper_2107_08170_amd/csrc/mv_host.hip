@@ -52,22 +52,21 @@ private:
     int prev_, target_ = -1;
 };
 
-constexpr size_t kLdsBudget = 64 * 1024;      // per-workgroup LDS the render kernel may ask for
-
 }  // namespace
 
 struct mv_batch {
     mv_config cfg{};
     int num_obs = 0;
     int voxels_per_env = 0;
-    int words_per_env = 0;
+    mv::GridLayout layout{};
+    mv::LdsPlan plan{};
     int materials_plus_one = 0;
     double tan_half_x = 0, tan_half_y = 0;
     float intensity[mv::kNumFaces] = {};
-    size_t lds_bytes = 0;
 
     uint8_t* d_vox = nullptr;
-    uint32_t* d_occ = nullptr;
+    uint64_t* d_bits = nullptr;
+    int32_t* d_ztop = nullptr;
     uint8_t* d_palette = nullptr;
     uint32_t* d_lut = nullptr;
     float* d_sx = nullptr;
@@ -84,7 +83,7 @@ struct mv_batch {
 static void free_batch(mv_batch* b)
 {
     if (!b) return;
-    (void)hipFree(b->d_vox); (void)hipFree(b->d_occ); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
+    (void)hipFree(b->d_vox); (void)hipFree(b->d_bits); (void)hipFree(b->d_ztop); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
     (void)hipFree(b->d_sx); (void)hipFree(b->d_sy); (void)hipFree(b->d_cams); (void)hipFree(b->d_self);
     (void)hipFree(b->d_rec);
     delete b;
@@ -133,11 +132,11 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     if (voxels > (1ll << 30)) return fail(MV_ERR_CAPACITY, "mv_create_batch: grid too large");
     const long long num_obs = (long long)cfg->num_envs * cfg->agents_per_env;
     if (num_obs > (1ll << 24)) return fail(MV_ERR_ARG, "mv_create_batch: more than 2^24 observations");
-    const int words = (int)((voxels + 31) / 32);
-    const size_t lds = mv::render_lds_bytes(words);
-    if (lds > kLdsBudget)
-        return fail(MV_ERR_CAPACITY, "mv_create_batch: occupancy bits of one grid need %zu bytes of LDS, budget is %zu",
-                    lds, kLdsBudget);
+    const mv::GridLayout layout = mv::make_layout(cfg->grid_x, cfg->grid_y, cfg->grid_z);
+    const mv::LdsPlan plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1);
+    if (plan.bytes == 0)
+        return fail(MV_ERR_CAPACITY, "mv_create_batch: the occupancy bit rows of one %dx%dx%d grid do not fit in %zu bytes of LDS",
+                    cfg->grid_x, cfg->grid_y, cfg->grid_z, mv::kLdsBudget);
 
     int device_count = 0;
     MV_HIP(hipGetDeviceCount(&device_count));
@@ -150,9 +149,9 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     b->cfg = *cfg;
     b->num_obs = (int)num_obs;
     b->voxels_per_env = (int)voxels;
-    b->words_per_env = words;
+    b->layout = layout;
+    b->plan = plan;
     b->materials_plus_one = cfg->num_materials + 1;
-    b->lds_bytes = lds;
     b->tan_half_x = std::tan(0.5 * (double)cfg->hfov_rad);
     b->tan_half_y = b->tan_half_x * (double)cfg->height / (double)cfg->width;
     // Face intensities are batch constants: ambient + diffuse * max(0, n.L) for the six axis
@@ -173,7 +172,8 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
         if (e == hipSuccess) e = hipMalloc(p, bytes);
     };
     alloc((void**)&b->d_vox, N * (size_t)voxels);
-    alloc((void**)&b->d_occ, N * (size_t)words * 4);
+    alloc((void**)&b->d_bits, N * (size_t)layout.env_words * 8);
+    alloc((void**)&b->d_ztop, N * 4);
     alloc((void**)&b->d_palette, N * (size_t)b->materials_plus_one * 3);
     alloc((void**)&b->d_lut, N * (size_t)mv::kNumFaces * b->materials_plus_one * 4);
     alloc((void**)&b->d_sx, (size_t)cfg->width * 4);
@@ -183,6 +183,7 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     alloc((void**)&b->d_rec, (size_t)num_obs * sizeof(mv::CameraRecord));
     if (e == hipSuccess) e = mv::launch_pixel_scalars(b->d_sx, b->d_sy, cfg->width, cfg->height, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e == hipSuccess) e = mv::prepare_render(plan.bytes);
     if (e != hipSuccess) {
         free_batch(b);
         return fail(MV_ERR_HIP, "mv_create_batch: device set-up failed: %s", hipGetErrorString(e));
@@ -206,7 +207,8 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
     const size_t pal_bytes = (size_t)b->materials_plus_one * 3;
     uint8_t* vox_dst = b->d_vox + (size_t)first_env * V;
     uint8_t* pal_dst = b->d_palette + (size_t)first_env * pal_bytes;
-    uint32_t* occ_dst = b->d_occ + (size_t)first_env * b->words_per_env;
+    uint64_t* bits_dst = b->d_bits + (size_t)first_env * b->layout.env_words;
+    int32_t* ztop_dst = b->d_ztop + first_env;
     uint32_t* lut_dst = b->d_lut + (size_t)first_env * mv::kNumFaces * b->materials_plus_one;
 
     if (!src_is_device) {
@@ -220,11 +222,11 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
         if (palette) MV_HIP(hipMemcpyAsync(pal_dst, palette, (size_t)count * pal_bytes, hipMemcpyHostToDevice, stream));
         // pageable host memory: make sure the runtime is done reading it before we return
         MV_HIP(hipStreamSynchronize(stream));
-        MV_HIP(mv::launch_pack(vox_dst, vox_dst, occ_dst, count, b->voxels_per_env, b->words_per_env, stream));
+        MV_HIP(mv::launch_pack(vox_dst, vox_dst, bits_dst, ztop_dst, count, b->layout, stream));
     } else {
         if (palette)
             MV_HIP(hipMemcpyAsync(pal_dst, palette, (size_t)count * pal_bytes, hipMemcpyDeviceToDevice, stream));
-        MV_HIP(mv::launch_pack(voxels, vox_dst, occ_dst, count, b->voxels_per_env, b->words_per_env, stream));
+        MV_HIP(mv::launch_pack(voxels, vox_dst, bits_dst, ztop_dst, count, b->layout, stream));
     }
     if (palette)
         MV_HIP(mv::launch_shade_tables(pal_dst, lut_dst, count, b->materials_plus_one, b->intensity, stream));
@@ -278,11 +280,12 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     if (!scope.ok()) return fail(MV_ERR_HIP, "mv_render_batch: cannot select device %d", b->cfg.device);
 
     mv::RenderParams p{};
-    p.occ = b->d_occ; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
+    p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
     p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
-    p.words_per_env = b->words_per_env;
+    p.g = b->layout;
     p.voxels_per_env = b->voxels_per_env;
-    p.X = b->cfg.grid_x; p.Y = b->cfg.grid_y; p.Z = b->cfg.grid_z;
+    p.lut_in_lds = b->plan.lut_in_lds;
+    p.threads = b->plan.threads;
     p.W = b->cfg.width; p.H = b->cfg.height; p.A = b->cfg.agents_per_env;
     p.materials_plus_one = b->materials_plus_one;
     p.tiles_x = (p.W + mv::kTile - 1) / mv::kTile;
@@ -296,7 +299,7 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
         long long per_obs = (target_blocks + b->num_obs - 1) / b->num_obs;
         if (per_obs < 1) per_obs = 1;
         tpb = (int)((p.tiles_per_obs + per_obs - 1) / per_obs);
-        const int min_tpb = mv::kWavesPerBlock * 2;
+        const int min_tpb = (p.threads / 64) * 2;
         if (tpb < min_tpb) tpb = min_tpb;
     }
     if (tpb > p.tiles_per_obs) tpb = p.tiles_per_obs;
@@ -307,8 +310,8 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.total_blocks = (uint32_t)total;
     p.blocks_per_xcd = (uint32_t)((total + mv::kXcds - 1) / mv::kXcds);
     p.sky_packed = (uint32_t)b->cfg.sky_rgb[0] | ((uint32_t)b->cfg.sky_rgb[1] << 8) | ((uint32_t)b->cfg.sky_rgb[2] << 16);
-    p.max_steps = p.X + p.Y + p.Z + 3;
-    MV_HIP(mv::launch_render(p, b->lds_bytes, (hipStream_t)hip_stream));
+    p.max_steps = p.g.X + p.g.Y + p.g.Z + 3;
+    MV_HIP(mv::launch_render(p, b->plan.bytes, (hipStream_t)hip_stream));
     return MV_OK;
 }
 
@@ -320,12 +323,17 @@ void mv_destroy(mv_batch* b)
     free_batch(b);
 }
 
-int mv_debug_occupancy(mv_batch* b, int32_t env, const uint32_t** words, int32_t* words_per_env)
+int mv_debug_occupancy(mv_batch* b, int32_t env, const uint64_t** x_rows, int32_t* x_row_words,
+                       const uint64_t** y_rows, int32_t* y_row_words, const int32_t** top_layer)
 {
-    if (!b || !words || !words_per_env) return fail(MV_ERR_ARG, "mv_debug_occupancy: null argument");
+    if (!b || !x_rows || !x_row_words || !y_rows || !y_row_words || !top_layer)
+        return fail(MV_ERR_ARG, "mv_debug_occupancy: null argument");
     if (env < 0 || env >= b->cfg.num_envs) return fail(MV_ERR_RANGE, "mv_debug_occupancy: env %d", env);
-    *words = b->d_occ + (size_t)env * b->words_per_env;
-    *words_per_env = b->words_per_env;
+    *x_rows = b->d_bits + (size_t)env * b->layout.env_words;
+    *x_row_words = b->layout.rowwords_x;
+    *y_rows = *x_rows + b->layout.xrow_words;
+    *y_row_words = b->layout.rowwords_y;
+    *top_layer = b->d_ztop + env;
     return MV_OK;
 }
 

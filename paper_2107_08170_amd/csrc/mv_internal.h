@@ -16,14 +16,27 @@ struct alignas(64) CameraRecord {
 };
 static_assert(sizeof(CameraRecord) == 64, "camera record must be 64 bytes");
 
-constexpr int kBlockThreads = 256;        // 4 wave64
-constexpr int kWavesPerBlock = kBlockThreads / 64;
 constexpr int kTile = 8;                  // a wave renders an 8x8 pixel tile
 constexpr int kXcds = 8;                  // MI355X: 8 XCDs, workgroups are dealt round-robin
 constexpr int kNumFaces = 7;              // six faces + "inside"
+constexpr size_t kLdsBudget = 160 * 1024; // LDS one workgroup may use on gfx950
+
+// Occupancy bits in device memory, per environment ("bit rows"):
+//   x rows: Z*Y rows of rowwords_x 64-bit words; row (k*Y + j), bit i   <-> voxel (i,j,k)
+//   y rows: Z*X rows of rowwords_y 64-bit words; row (k*X + i), bit j   <-> voxel (i,j,k)
+// A ray mostly along x scans x rows, one mostly along y scans y rows: a whole run of cells along
+// the row is tested with one shift, instead of one DDA step per cell.
+struct GridLayout {
+    int32_t X, Y, Z;
+    int32_t rowwords_x, rowwords_y;       // 64-bit words per row
+    int32_t xrow_words, yrow_words;       // 64-bit words of the x-row / y-row arrays of one environment
+    int32_t env_words;                    // xrow_words + yrow_words
+    int32_t fast;                         // 1: X,Y <= 64 (one word per row) -> row-scan traversal
+};
 
 struct RenderParams {
-    const uint32_t*     occ;              // [N][words_per_env] occupancy bits, bit = linear voxel index
+    const uint64_t*     bits;             // [N][env_words]
+    const int32_t*      ztop;             // [N] 1 + highest solid layer (0 = empty world)
     const uint8_t*      vox;              // [N][V] material ids
     const uint32_t*     lut;              // [N][7][M+1] shaded colours, r | g<<8 | b<<16
     const CameraRecord* rec;              // [N*A]
@@ -34,25 +47,37 @@ struct RenderParams {
     uint8_t*            aux_material;     // or nullptr
     int32_t*            aux_hit;          // or nullptr
     uint8_t*            aux_face;         // or nullptr
-    int32_t words_per_env;
+    GridLayout g;
     int32_t voxels_per_env;
-    int32_t X, Y, Z, W, H, A;
+    int32_t W, H, A;
     int32_t materials_plus_one;
+    int32_t lut_in_lds;                   // 1: the colour table of the environment is staged in LDS
     int32_t tiles_x, tiles_per_obs, tiles_per_block, blocks_per_obs;
     uint32_t total_blocks, blocks_per_xcd;
     uint32_t sky_packed;
     int32_t max_steps;
+    int32_t threads;                      // workgroup size (multiple of 64)
 };
+
+GridLayout make_layout(int X, int Y, int Z);
+
+// LDS plan of the render kernel for a batch; returns 0 if the grid cannot be staged at all.
+struct LdsPlan {
+    size_t bytes;         // dynamic LDS per workgroup
+    int    threads;       // workgroup size that keeps a CU busy with that much LDS
+    int    lut_in_lds;
+};
+LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one);
 
 // Launchers (mv_kernels.hip).  All enqueue on `stream` and return hipGetLastError().
 hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t stream);
-hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint32_t* occ_dst, int count,
-                       int voxels_per_env, int words_per_env, hipStream_t stream);
+hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
+                       const GridLayout& g, hipStream_t stream);
 hipError_t launch_shade_tables(const uint8_t* palette, uint32_t* lut, int count, int materials_plus_one,
                                const float intensity[kNumFaces], hipStream_t stream);
 hipError_t launch_cameras(const float* cams, const int32_t* self_voxel, CameraRecord* rec, int num_obs,
                           double tan_half_x, double tan_half_y, int plane_voxels, hipStream_t stream);
+hipError_t prepare_render(size_t lds_bytes);
 hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t stream);
-size_t render_lds_bytes(int words_per_env);
 
 }  // namespace mv

@@ -1,18 +1,79 @@
 // HIP kernels (gfx950 / CDNA4) of the batched voxel-world renderer.
 //
 // Hot path (paper Sec. 3.2, Eq. 2: O = Render(S), all N*A views in one GPU request):
-//   pack      : material ids -> occupancy bits                       (once per world upload)
+//   pack      : material ids -> occupancy "bit rows" along x and along y (once per world upload)
 //   shade     : palette x face intensity -> per-environment colour table
 //   cameras   : (x,y,z,yaw,pitch) -> 64-byte camera records (float64 trig, float32 result)
-//   render    : one workgroup stages one environment's occupancy bits in LDS; each wave renders
-//               8x8-pixel tiles, one pixel ray per lane, 3D-DDA through the bit grid; colour and
-//               depth leave as row-major dword stores.
+//   render    : a workgroup stages one environment's bit rows in LDS (plus mirrored copies, so that
+//               every ray scans towards increasing bit positions); each wave renders 8x8-pixel
+//               tiles, one pixel ray per lane.  The traversal is a DDA over the (v,z) rows the ray
+//               passes through, where u is the ray's dominant horizontal axis: all cells the ray
+//               covers inside one row are tested with a single 64-bit shift.  Colour and depth
+//               leave as row-major dword stores.
 // No MFMA anywhere: nothing on this path is a dense contraction.
 #include "mv_internal.h"
 
 #include <math.h>
 
 namespace mv {
+
+// ------------------------------------------------------------------------------------------
+// layout helpers (host)
+// ------------------------------------------------------------------------------------------
+GridLayout make_layout(int X, int Y, int Z)
+{
+    GridLayout g{};
+    g.X = X; g.Y = Y; g.Z = Z;
+    g.rowwords_x = (X + 63) / 64;
+    g.rowwords_y = (Y + 63) / 64;
+    g.xrow_words = Z * Y * g.rowwords_x;
+    g.yrow_words = Z * X * g.rowwords_y;
+    g.env_words = g.xrow_words + g.yrow_words;
+    g.fast = (X <= 64 && Y <= 64) ? 1 : 0;
+    return g;
+}
+
+static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
+
+// LDS map (bytes):  [sx: W floats][sy: H floats] | [4 scan-class records, 64 B each] |
+//                   [colour table 7*(M+1) dwords, optional] | bit rows
+// fast grids stage four row arrays (x, x mirrored, y, y mirrored); others stage the x rows only.
+struct LdsMap {
+    uint32_t scalars, classes, lut, rows;
+    uint32_t total;
+};
+
+static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one, bool lut_in_lds)
+{
+    LdsMap m{};
+    size_t off = 0;
+    m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
+    m.classes = (uint32_t)off; off += 4 * 64;
+    m.lut = (uint32_t)off;
+    if (lut_in_lds) off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
+    m.rows = (uint32_t)off;
+    off += g.fast ? 2 * (size_t)g.env_words * 8 : (size_t)g.xrow_words * 8;
+    m.total = (uint32_t)off;
+    return m;
+}
+
+LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one)
+{
+    LdsPlan plan{};
+    size_t rows = g.fast ? 2 * (size_t)g.env_words * 8 : (size_t)g.xrow_words * 8;
+    if (rows + (size_t)(W + H) * 4 + 1024 > kLdsBudget) return plan;       // bytes == 0: does not fit
+    plan.lut_in_lds = 1;
+    LdsMap m = lds_map(g, W, H, materials_plus_one, true);
+    if (m.total > kLdsBudget) {
+        plan.lut_in_lds = 0;
+        m = lds_map(g, W, H, materials_plus_one, false);
+    }
+    plan.bytes = m.total;
+    // keep at least ~16 waves resident per CU whatever one workgroup's LDS share is
+    size_t per_cu = kLdsBudget / plan.bytes;
+    plan.threads = per_cu >= 4 ? 256 : (per_cu >= 2 ? 512 : 1024);
+    return plan;
+}
 
 // ------------------------------------------------------------------------------------------
 // pixel-centre scalars: sx[c] = (2c+1-W)/W, sy[r] = (H-2r-1)/H, one correctly rounded divide each
@@ -32,57 +93,72 @@ hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t 
 }
 
 // ------------------------------------------------------------------------------------------
-// pack: one thread per 32-voxel word.  Reads 32 material bytes, writes them back to the batch's
-// own grid (unless the upload already landed there) and one occupancy word.
+// pack: one workgroup per environment.  Each wave takes whole z layers: the layer's material bytes
+// go through LDS (coalesced global reads, and the copy into the batch's own grid), then every bit
+// row is one wave ballot: lane = position along the row.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
-                                                   uint32_t* __restrict__ occ_dst, int voxels_per_env,
-                                                   int words_per_env, long long total_words, int vec_ok)
+constexpr int kPackThreads = 256;
+
+__global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
+                                                            uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
+                                                            GridLayout g)
 {
-    long long gw = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (gw >= total_words) return;
-    int env = (int)(gw / words_per_env);
-    int w = (int)(gw - (long long)env * words_per_env);
-    long long base = (long long)env * voxels_per_env + (long long)w * 32;
-    int n = voxels_per_env - w * 32;
-    if (n > 32) n = 32;
-    uint32_t bits = 0;
+    extern __shared__ uint8_t layer_lds[];                 // one layer per wave, padded to 16 bytes
+    __shared__ int top_lds;
+    const int env = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int waves = kPackThreads / 64;
+    const int XY = g.X * g.Y;
+    const int layer_stride = (XY + 15) & ~15;
+    uint8_t* mine = layer_lds + (size_t)wave * layer_stride;
+    const size_t env_vox = (size_t)env * XY * g.Z;
     const bool copy = (src != vox_dst);
-    if (vec_ok && n == 32) {
-        const uint4* s4 = reinterpret_cast<const uint4*>(src + base);
-        uint4 a = s4[0], b = s4[1];
-        uint32_t v[8] = { a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w };
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            uint32_t x = v[q];
-            uint32_t nz = ((x & 0xffu) != 0) | (((x & 0xff00u) != 0) << 1) | (((x & 0xff0000u) != 0) << 2) |
-                          (((x & 0xff000000u) != 0) << 3);
-            bits |= nz << (4 * q);
+    uint64_t* xrows = bits_dst + (size_t)env * g.env_words;
+    uint64_t* yrows = xrows + g.xrow_words;
+    if (threadIdx.x == 0) top_lds = 0;
+    __syncthreads();
+    int top = 0;
+
+    for (int k = wave; k < g.Z; k += waves) {
+        const uint8_t* lsrc = src + env_vox + (size_t)k * XY;
+        for (int b = lane; b < XY; b += 64) {
+            uint8_t m = lsrc[b];
+            mine[b] = m;
+            if (copy) vox_dst[env_vox + (size_t)k * XY + b] = m;
         }
-        if (copy) {
-            uint4* d4 = reinterpret_cast<uint4*>(vox_dst + base);
-            d4[0] = a;
-            d4[1] = b;
-        }
-    } else {
-        for (int q = 0; q < n; ++q) {
-            uint8_t m = src[base + q];
-            bits |= (uint32_t)(m != 0) << q;
-            if (copy) vox_dst[base + q] = m;
-        }
+        __builtin_amdgcn_wave_barrier();
+        // x rows: row (k*Y + j), word w, bit = i - 64w
+        bool any = false;
+        for (int j = 0; j < g.Y; ++j)
+            for (int w = 0; w < g.rowwords_x; ++w) {
+                int i = w * 64 + lane;
+                bool s = i < g.X && mine[j * g.X + i] != 0;
+                uint64_t mask = __ballot(s);
+                any |= mask != 0;
+                if (lane == 0) xrows[((size_t)k * g.Y + j) * g.rowwords_x + w] = mask;
+            }
+        // y rows: row (k*X + i), word w, bit = j - 64w
+        for (int i = 0; i < g.X; ++i)
+            for (int w = 0; w < g.rowwords_y; ++w) {
+                int j = w * 64 + lane;
+                bool s = j < g.Y && mine[j * g.X + i] != 0;
+                uint64_t mask = __ballot(s);
+                if (lane == 0) yrows[((size_t)k * g.X + i) * g.rowwords_y + w] = mask;
+            }
+        if (any) top = k + 1;
+        __builtin_amdgcn_wave_barrier();
     }
-    occ_dst[gw] = bits;
+    if (lane == 0) atomicMax(&top_lds, top);
+    __syncthreads();
+    if (threadIdx.x == 0) ztop_dst[env] = top_lds;
 }
 
-hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint32_t* occ_dst, int count, int voxels_per_env,
-                       int words_per_env, hipStream_t stream)
+hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
+                       const GridLayout& g, hipStream_t stream)
 {
-    long long total = (long long)count * words_per_env;
-    int vec_ok = (voxels_per_env % 32 == 0) && ((reinterpret_cast<uintptr_t>(src) & 15) == 0) &&
-                 ((reinterpret_cast<uintptr_t>(vox_dst) & 15) == 0);
-    unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, stream, src, vox_dst, occ_dst, voxels_per_env,
-                       words_per_env, total, vec_ok);
+    size_t layer_stride = ((size_t)g.X * g.Y + 15) & ~(size_t)15;
+    size_t lds = layer_stride * (kPackThreads / 64);
+    hipLaunchKernelGGL(pack_kernel, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst, g);
     return hipGetLastError();
 }
 
@@ -169,18 +245,44 @@ struct Hit {
     float t;        // planar depth
 };
 
-// One ray through the LDS-resident bit grid.  Crossing parameters are recomputed as
-// t = n*|1/d| + t_first (one fused op, error relative to t itself) rather than accumulated, so the
-// position error at any crossing stays a few 1e-6 voxels across the whole grid.
-template <bool HAS_SELF>
-__device__ __forceinline__ Hit trace_ray(const uint32_t* __restrict__ occ, const float P[3], const float d[3],
-                                         int X, int Y, int Z, bool origin_in_grid, int self_lo, int self_hi,
-                                         int max_steps)
+constexpr float kBig = 3.0e38f;            // stands in for 1/0: keeps every product finite or +inf, never NaN
+
+__device__ __forceinline__ float safe_rcp(float d)
+{
+    // v_rcp_f32 (1 ulp) then clamp: +-inf for d = +-0 becomes +-kBig
+    return __builtin_amdgcn_fmed3f(__builtin_amdgcn_rcpf(d), -kBig, kBig);
+}
+
+// Constants of one scan class of one camera.  A class is (dominant horizontal axis, direction):
+// 0: +x, 1: -x, 2: +y, 3: -y.  u is the scan axis, v the other horizontal axis.  For the negative
+// directions the class works in mirrored coordinates u' = U - u against a bit-reversed copy of the
+// rows, so that inside the traversal every ray runs towards increasing bit positions.
+struct alignas(16) ScanClass {
+    float Pu;           // camera coordinate along u (mirrored for classes 1, 3)
+    float uexit;        // U - Pu: distance to the far side of the grid along u
+    float hi_v, lo_v;   // distances from the camera to the upper / lower plane of its cell along v
+    float nv_pos, nv_neg;   // v planes between the camera cell and the grid boundary, each direction
+    int   addr0;        // LDS byte address of the camera's row in this class's row array
+    int   i0;           // camera cell along u (mirrored)
+    int   zstride;      // bytes between rows of consecutive layers: 8 * V
+    int   um1;          // U - 1
+    int   j0;           // camera cell along v
+    int   face_u;       // face code of a voxel found while scanning along the row
+    int   face_v;       // face code of a -v face (add 1 for +v)
+    int   mirror_a, mirror_b;   // original u cell = mirror_a + mirror_b * (mirrored cell)
+    int   pad;
+};
+static_assert(sizeof(ScanClass) == 64, "scan class record must be 64 bytes");
+
+// Plain 3D-DDA through the x rows (any row width).  Used for cameras outside the grid and for grids
+// wider than 64 voxels.  Crossing parameters are t = n*|1/d| + t_first (one fused op, error relative
+// to t itself) rather than accumulated.
+__device__ __forceinline__ Hit trace_generic(const uint32_t* __restrict__ xrows32, int rowdwords, const float P[3],
+                                             const float d[3], int X, int Y, int Z, bool origin_in_grid, int max_steps)
 {
     const float kInf = __builtin_inff();
     const int dim[3] = { X, Y, Z };
     Hit miss = { -1, 255, 0.0f };
-
     float inv[3];
     bool pos[3], zero[3];
 #pragma unroll
@@ -189,10 +291,9 @@ __device__ __forceinline__ Hit trace_ray(const uint32_t* __restrict__ occ, const
         pos[a] = d[a] > 0.0f;
         inv[a] = zero[a] ? 0.0f : __builtin_amdgcn_rcpf(d[a]);
     }
-
     float t0 = 0.0f;
     int entry_axis = -1;
-    if (!origin_in_grid) {                       // wave-uniform: the camera is the same for the tile
+    if (!origin_in_grid) {
         float t_near = -kInf, t_far = kInf;
         bool dead = false;
 #pragma unroll
@@ -209,68 +310,132 @@ __device__ __forceinline__ Hit trace_ray(const uint32_t* __restrict__ occ, const
         if (dead || t_near > t_far || t_far < 0.0f) return miss;
         if (t_near > 0.0f) t0 = t_near; else entry_axis = -1;
     }
-
-    int cell[3];
+    int cell[3], step[3];
     float t_next[3], t_first[3], dt[3], n[3];
-    int stride[3] = { 1, X, X * Y };
-    float t_exit = kInf;                          // parameter at which the ray leaves the grid box
+    float t_exit = kInf;
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
         float q = floorf(fmaf(t0, d[a], P[a]));
         int c = (int)fminf(fmaxf(q, 0.0f), (float)(dim[a] - 1));
         if (a == entry_axis) c = pos[a] ? 0 : dim[a] - 1;
         cell[a] = c;
+        step[a] = pos[a] ? 1 : -1;
         float plane = (float)(c + (pos[a] ? 1 : 0));
         t_first[a] = zero[a] ? kInf : (plane - P[a]) * inv[a];
         dt[a] = fabsf(inv[a]);
         n[a] = 0.0f;
         t_next[a] = t_first[a];
-        // number of planes between the current cell and the outside of the grid, this axis
         float planes_left = (float)(pos[a] ? dim[a] - 1 - c : c);
         float te = zero[a] ? kInf : fmaf(planes_left, dt[a], t_first[a]);
         t_exit = fminf(t_exit, te);
-        if (!pos[a]) stride[a] = -stride[a];
     }
-
-    int idx = (cell[2] * Y + cell[1]) * X + cell[0];
-    float t_hit = t0;
-    int face = entry_axis >= 0 ? 2 * entry_axis + (pos[entry_axis] ? 0 : 1) : 6;
-
-    auto solid = [&](int i) -> bool {
-        bool s = (occ[i >> 5] >> (i & 31)) & 1u;
-        if (HAS_SELF) s = s && i != self_lo && i != self_hi;
-        return s;
+    auto solid = [&](int i, int j, int k) -> bool {
+        return (xrows32[(k * Y + j) * rowdwords + (i >> 5)] >> (i & 31)) & 1u;
     };
-    if (solid(idx)) return Hit{ idx, face, t_hit };
-
+    int face = entry_axis >= 0 ? 2 * entry_axis + (pos[entry_axis] ? 0 : 1) : 6;
+    if (solid(cell[0], cell[1], cell[2])) return Hit{ (cell[2] * Y + cell[1]) * X + cell[0], face, t0 };
     for (int it = 0; it < max_steps; ++it) {
         float tm = fminf(fminf(t_next[0], t_next[1]), t_next[2]);
-        // leaving the grid: the exit parameter was built from the same n*dt+t_first expression, so
-        // this comparison is exact
         if (!(tm < t_exit)) return miss;
         bool cx = (t_next[0] <= t_next[1]) & (t_next[0] <= t_next[2]);
         bool cy = !cx & (t_next[1] <= t_next[2]);
         bool cz = !cx & !cy;
-        n[0] += cx ? 1.0f : 0.0f;
-        n[1] += cy ? 1.0f : 0.0f;
-        n[2] += cz ? 1.0f : 0.0f;
-        idx += cx ? stride[0] : (cy ? stride[1] : stride[2]);
+        n[0] += cx ? 1.0f : 0.0f;  cell[0] += cx ? step[0] : 0;
+        n[1] += cy ? 1.0f : 0.0f;  cell[1] += cy ? step[1] : 0;
+        n[2] += cz ? 1.0f : 0.0f;  cell[2] += cz ? step[2] : 0;
         t_next[0] = fmaf(n[0], dt[0], t_first[0]);
         t_next[1] = fmaf(n[1], dt[1], t_first[1]);
         t_next[2] = fmaf(n[2], dt[2], t_first[2]);
-        if (solid(idx)) {
+        if (solid(cell[0], cell[1], cell[2])) {
             int axis = cx ? 0 : (cy ? 1 : 2);
             bool p = cx ? pos[0] : (cy ? pos[1] : pos[2]);
-            return Hit{ idx, 2 * axis + (p ? 0 : 1), tm };
+            return Hit{ (cell[2] * Y + cell[1]) * X + cell[0], 2 * axis + (p ? 0 : 1), tm };
         }
     }
     return miss;
 }
 
-template <bool AUX, bool PACKED>
-__global__ __launch_bounds__(kBlockThreads) void render_kernel(RenderParams p)
+// Row-scan traversal: DDA over the (v,z) rows, one 64-bit shift per row.
+//   zc: uniform z constants {hi_z, lo_z, nz_pos, nz_neg} and k0
+__device__ __forceinline__ Hit trace_rows(const uint8_t* __restrict__ lds, uint32_t classes_off, float dx, float dy,
+                                          float dz, float hi_z, float lo_z, float nz_pos, float nz_neg, int k0, int X,
+                                          int Y, int max_steps)
 {
-    extern __shared__ uint32_t lds_occ[];
+    const bool xm = fabsf(dx) >= fabsf(dy);
+    const float du = xm ? dx : dy;
+    const float dv = xm ? dy : dx;
+    const int q = (xm ? 0 : 2) + (du < 0.0f ? 1 : 0);
+    const ScanClass c = *reinterpret_cast<const ScanClass*>(lds + classes_off + q * 64);
+
+    const float dua = fabsf(du);
+    const float inv_u = safe_rcp(dua);
+    const float inv_v = safe_rcp(dv);
+    const float inv_z = safe_rcp(dz);
+    const float dt_v = fabsf(inv_v), dt_z = fabsf(inv_z);
+    // first crossing on an axis: (upper plane - P)/d if d > 0, (lower plane - P)/d otherwise; the other
+    // candidate is <= 0, so the maximum picks the right one without a compare
+    const float t0_v = fmaxf(c.hi_v * inv_v, c.lo_v * inv_v);
+    const float t0_z = fmaxf(hi_z * inv_z, lo_z * inv_z);
+    // leaving the grid: same n*dt + t0 expression as the crossings, so the comparison below is exact
+    const float t_end = fminf(fminf(c.uexit * inv_u, fmaf(dv < 0.0f ? c.nv_neg : c.nv_pos, dt_v, t0_v)),
+                              fmaf(dz < 0.0f ? nz_neg : nz_pos, dt_z, t0_z));
+    const int sv = dv < 0.0f ? -8 : 8;
+    const int sz = dz < 0.0f ? -c.zstride : c.zstride;
+
+    float t_v = t0_v, t_z = t0_z, n_v = 0.0f, n_z = 0.0f;
+    int i_cur = c.i0, addr = c.addr0;
+    uint64_t r = 0;
+    bool found = false;
+    for (int it = 0; it < max_steps; ++it) {
+        const uint64_t row = *reinterpret_cast<const uint64_t*>(lds + addr);
+        const float t_out = fminf(t_v, t_z);
+        const float u_out = fmaf(t_out, dua, c.Pu);
+        const int i_out = min((int)u_out, c.um1);
+        r = row >> i_cur;                                   // drop the cells behind the ray
+        const uint64_t in_range = r << (63 - (i_out - i_cur));   // keep the cells up to where the ray leaves the row
+        if (in_range != 0) { found = true; break; }
+        if (!(t_out < t_end)) break;
+        const bool cv = t_v <= t_z;
+        const float one = cv ? 1.0f : 0.0f;
+        n_v += one;
+        n_z += 1.0f - one;
+        addr += cv ? sv : sz;
+        t_v = fmaf(n_v, dt_v, t0_v);
+        t_z = fmaf(n_z, dt_z, t0_z);
+        i_cur = i_out;
+    }
+    if (!found) return Hit{ -1, 255, 0.0f };
+
+    const int f = __builtin_ctzll(r);
+    const int iu = i_cur + f;                               // mirrored cell along u
+    // the row was entered at the later of the last v crossing and the last z crossing (n-1; for n = 0
+    // the expression is <= 0 because the first plane is at most one cell away)
+    const float tv_last = fmaf(n_v - 1.0f, dt_v, t0_v);
+    const float tz_last = fmaf(n_z - 1.0f, dt_z, t0_z);
+    const bool via_z = tz_last >= tv_last;
+    const float t_in = fmaxf(fmaxf(tv_last, tz_last), 0.0f);
+    const bool started_here = (n_v + n_z) == 0.0f;
+    int face;
+    float t;
+    if (f != 0) {
+        face = c.face_u;
+        t = ((float)iu - c.Pu) * inv_u;
+    } else {
+        face = started_here ? 6 : (via_z ? 4 + (dz < 0.0f ? 1 : 0) : c.face_v + (dv < 0.0f ? 1 : 0));
+        t = t_in;
+    }
+    const int jv = c.j0 + (dv < 0.0f ? -(int)n_v : (int)n_v);
+    const int k = k0 + (dz < 0.0f ? -(int)n_z : (int)n_z);
+    const int io = c.mirror_a + c.mirror_b * iu;
+    const int idx = xm ? (k * Y + jv) * X + io : (k * Y + io) * X + jv;
+    return Hit{ idx, face, t };
+}
+
+template <bool AUX, bool PACKED, bool FAST>
+__global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    const int threads = p.threads;
 
     // XCD-aware mapping: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous range
     // of work items so that the blocks sharing an environment also share an L2.
@@ -280,55 +445,151 @@ __global__ __launch_bounds__(kBlockThreads) void render_kernel(RenderParams p)
     const int obs = (int)(work / (uint32_t)p.blocks_per_obs);
     const int part = (int)(work - (uint32_t)obs * (uint32_t)p.blocks_per_obs);
     const int env = obs / p.A;
+    const GridLayout& g = p.g;
+    const int X = g.X, Y = g.Y, Z = g.Z;
 
-    {   // a3: stage this environment's occupancy bits
-        const uint32_t* g = p.occ + (size_t)env * p.words_per_env;
-        if ((p.words_per_env & 3) == 0) {
-            const uint4* g4 = reinterpret_cast<const uint4*>(g);
-            uint4* l4 = reinterpret_cast<uint4*>(lds_occ);
-            for (int w = threadIdx.x; w < (p.words_per_env >> 2); w += kBlockThreads) l4[w] = g4[w];
+    // LDS map, mirrors lds_map() on the host
+    const uint32_t off_scalars = 0;
+    const uint32_t off_classes = (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
+    const uint32_t off_lut = off_classes + 256;
+    const uint32_t off_rows = off_lut + (p.lut_in_lds ? (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15) : 0u);
+    float* lds_sx = reinterpret_cast<float*>(lds + off_scalars);
+    float* lds_sy = lds_sx + p.W;
+    uint64_t* lds_rows = reinterpret_cast<uint64_t*>(lds + off_rows);
+
+    const CameraRecord& rec = p.rec[obs];
+    const float P[3] = { rec.P[0], rec.P[1], rec.P[2] };
+    const int self_lo = rec.self_lo;
+
+    {   // a3: stage pixel scalars, colour table and this environment's bit rows
+        for (int i = threadIdx.x; i < p.W; i += threads) lds_sx[i] = p.sx[i];
+        for (int i = threadIdx.x; i < p.H; i += threads) lds_sy[i] = p.sy[i];
+        if (p.lut_in_lds) {
+            const uint32_t* gl = p.lut + (size_t)env * kNumFaces * p.materials_plus_one;
+            uint32_t* ll = reinterpret_cast<uint32_t*>(lds + off_lut);
+            for (int i = threadIdx.x; i < kNumFaces * p.materials_plus_one; i += threads) ll[i] = gl[i];
+        }
+        const uint64_t* gb = p.bits + (size_t)env * g.env_words;
+        if (FAST) {
+            // arrays: [x rows][x rows mirrored][y rows][y rows mirrored]
+            uint64_t* ax = lds_rows;
+            uint64_t* axm = ax + g.xrow_words;
+            uint64_t* ay = axm + g.xrow_words;
+            uint64_t* aym = ay + g.yrow_words;
+            for (int w = threadIdx.x; w < g.xrow_words; w += threads) {
+                uint64_t v = gb[w];
+                ax[w] = v;
+                axm[w] = __brevll(v) >> (64 - X);
+            }
+            for (int w = threadIdx.x; w < g.yrow_words; w += threads) {
+                uint64_t v = gb[g.xrow_words + w];
+                ay[w] = v;
+                aym[w] = __brevll(v) >> (64 - Y);
+            }
         } else {
-            for (int w = threadIdx.x; w < p.words_per_env; w += kBlockThreads) lds_occ[w] = g[w];
+            for (int w = threadIdx.x; w < g.xrow_words; w += threads) lds_rows[w] = gb[w];
         }
     }
     __syncthreads();
 
-    const CameraRecord& rec = p.rec[obs];
-    const float P[3] = { rec.P[0], rec.P[1], rec.P[2] };
-    const int self_lo = rec.self_lo, self_hi = rec.self_hi;
-    const bool origin_in_grid = P[0] >= 0.0f && P[0] <= (float)p.X && P[1] >= 0.0f && P[1] <= (float)p.Y &&
-                                P[2] >= 0.0f && P[2] <= (float)p.Z;
+    const bool origin_in_grid = P[0] >= 0.0f && P[0] <= (float)X && P[1] >= 0.0f && P[1] <= (float)Y &&
+                                P[2] >= 0.0f && P[2] <= (float)Z;
+    const int k0 = min(max((int)floorf(P[2]), 0), Z - 1);
+
+    // This workgroup's copy of the rows is private to one camera: remove the camera's own body from it
+    // once, instead of testing for it at every step.
+    if (self_lo >= 0 && threadIdx.x < 2) {
+        int s = threadIdx.x == 0 ? self_lo : rec.self_hi;
+        if (s >= 0 && s < X * Y * Z) {
+            int k = s / (X * Y), rem = s - k * X * Y, j = rem / X, i = rem - j * X;
+            if (FAST) {
+                uint64_t* ax = lds_rows;
+                uint64_t* axm = ax + g.xrow_words;
+                uint64_t* ay = axm + g.xrow_words;
+                uint64_t* aym = ay + g.yrow_words;
+                ax[k * Y + j] &= ~(1ull << i);
+                axm[k * Y + j] &= ~(1ull << (X - 1 - i));
+                ay[k * X + i] &= ~(1ull << j);
+                aym[k * X + i] &= ~(1ull << (Y - 1 - j));
+            } else {
+                lds_rows[(k * Y + j) * g.rowwords_x + (i >> 6)] &= ~(1ull << (i & 63));
+            }
+        }
+    }
+    if (FAST && threadIdx.x >= 64 && threadIdx.x < 68) {
+        const int q = threadIdx.x - 64;
+        const bool xmaj = q < 2, neg = q & 1;
+        const int U = xmaj ? X : Y, V = xmaj ? Y : X;
+        const float pu = xmaj ? P[0] : P[1], pv = xmaj ? P[1] : P[0];
+        ScanClass c;
+        c.Pu = neg ? (float)U - pu : pu;
+        c.uexit = (float)U - c.Pu;
+        c.i0 = min(max((int)floorf(c.Pu), 0), U - 1);
+        c.j0 = min(max((int)floorf(pv), 0), V - 1);
+        c.hi_v = (float)(c.j0 + 1) - pv;
+        c.lo_v = (float)c.j0 - pv;
+        c.nv_pos = (float)(V - 1 - c.j0);
+        c.nv_neg = (float)c.j0;
+        const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? g.xrow_words : 0)
+                                                                   : 2 * g.xrow_words + (neg ? g.yrow_words : 0));
+        c.addr0 = (int)(array_off + 8u * (uint32_t)(k0 * V + c.j0));
+        c.zstride = 8 * V;
+        c.um1 = U - 1;
+        c.face_u = 2 * (xmaj ? 0 : 1) + (neg ? 1 : 0);
+        c.face_v = 2 * (xmaj ? 1 : 0);
+        c.mirror_a = neg ? U - 1 : 0;
+        c.mirror_b = neg ? -1 : 1;
+        c.pad = 0;
+        *reinterpret_cast<ScanClass*>(lds + off_classes + q * 64) = c;
+    }
+    __syncthreads();
+
+    // z constants are the same for every ray of the camera.  Above the highest solid layer of the
+    // environment a rising ray can only miss, so the grid is cut there.
+    const int ztop = p.ztop[env];
+    const int zlim = ztop > k0 ? ztop : Z;
+    const float hi_z = (float)(k0 + 1) - P[2], lo_z = (float)k0 - P[2];
+    const float nz_pos = (float)(zlim - 1 - k0), nz_neg = (float)k0;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int waves = threads >> 6;
     const int lane = threadIdx.x & 63;
     const int tile_begin = part * p.tiles_per_block;
     const int tile_end = min(tile_begin + p.tiles_per_block, p.tiles_per_obs);
     const size_t obs_pix = (size_t)obs * p.H * p.W;
+    const uint8_t* vox_env = p.vox + (size_t)env * p.voxels_per_env;
+    const uint32_t* lut_env = p.lut + (size_t)env * kNumFaces * p.materials_plus_one;
+    const uint32_t* lut_lds = reinterpret_cast<const uint32_t*>(lds + off_lut);
 
-    for (int tile = tile_begin + wave; tile < tile_end; tile += kWavesPerBlock) {
+    for (int tile = tile_begin + wave; tile < tile_end; tile += waves) {
         const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
         const int col = tx * kTile + (lane & 7), row = ty * kTile + (lane >> 3);
         const bool active = col < p.W && row < p.H;
         const int ccol = min(col, p.W - 1), crow = min(row, p.H - 1);
 
         // a4: ray through the pixel centre, two fused multiply-adds per axis
-        const float sx = p.sx[ccol], sy = p.sy[crow];
+        const float sx = lds_sx[ccol], sy = lds_sy[crow];
         float d[3];
 #pragma unroll
         for (int a = 0; a < 3; ++a) d[a] = fmaf(sy, rec.U[a], fmaf(sx, rec.R[a], rec.F[a]));
 
         // a5: traversal
-        Hit h = (self_lo >= 0)
-                    ? trace_ray<true>(lds_occ, P, d, p.X, p.Y, p.Z, origin_in_grid, self_lo, self_hi, p.max_steps)
-                    : trace_ray<false>(lds_occ, P, d, p.X, p.Y, p.Z, origin_in_grid, -1, -1, p.max_steps);
+        Hit h;
+        if (FAST && origin_in_grid)
+            h = trace_rows(lds, off_classes, d[0], d[1], d[2], hi_z, lo_z, nz_pos, nz_neg, k0, X, Y, p.max_steps);
+        else
+            h = trace_generic(reinterpret_cast<const uint32_t*>(lds_rows), 2 * g.rowwords_x, P, d, X, Y, Z,
+                              origin_in_grid, p.max_steps);
 
         // a6: shade
         uint32_t colour = p.sky_packed;
         int material = 0;
         if (h.idx >= 0) {
-            material = p.vox[(size_t)env * p.voxels_per_env + h.idx];
-            int m = min(material, p.materials_plus_one - 1);
-            colour = p.lut[((size_t)env * kNumFaces + h.face) * p.materials_plus_one + m];
+            const int safe_idx = min(h.idx, p.voxels_per_env - 1);
+            material = vox_env[safe_idx];
+            const int m = min(material, p.materials_plus_one - 1);
+            const int li = h.face * p.materials_plus_one + m;
+            colour = p.lut_in_lds ? lut_lds[li] : lut_env[li];
         }
 
         // a7: stores
@@ -360,23 +621,39 @@ __global__ __launch_bounds__(kBlockThreads) void render_kernel(RenderParams p)
     }
 }
 
-size_t render_lds_bytes(int words_per_env)
+template <bool AUX, bool PACKED, bool FAST>
+static hipError_t set_lds_limit(size_t lds_bytes)
 {
-    return ((size_t)words_per_env * 4 + 15) & ~(size_t)15;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<AUX, PACKED, FAST>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+}
+
+hipError_t prepare_render(size_t lds_bytes)
+{
+    if (lds_bytes <= 48 * 1024) return hipSuccess;
+    hipError_t e = hipSuccess;
+#define MV_SET(A, P, F) if (e == hipSuccess) e = set_lds_limit<A, P, F>(lds_bytes)
+    MV_SET(false, false, false); MV_SET(false, false, true); MV_SET(false, true, false); MV_SET(false, true, true);
+    MV_SET(true, false, false);  MV_SET(true, false, true);  MV_SET(true, true, false);  MV_SET(true, true, true);
+#undef MV_SET
+    return e;
 }
 
 hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t stream)
 {
     const bool aux = p.aux_material || p.aux_hit || p.aux_face;
     const bool packed = (p.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(p.rgb) & 3) == 0);
-    dim3 grid(p.blocks_per_xcd * kXcds), block(kBlockThreads);
+    const bool fast = p.g.fast != 0;
+    dim3 grid(p.blocks_per_xcd * kXcds), block(p.threads);
+#define MV_LAUNCH(A, P, F) hipLaunchKernelGGL((render_kernel<A, P, F>), grid, block, lds_bytes, stream, p)
     if (aux) {
-        if (packed) hipLaunchKernelGGL((render_kernel<true, true>), grid, block, lds_bytes, stream, p);
-        else        hipLaunchKernelGGL((render_kernel<true, false>), grid, block, lds_bytes, stream, p);
+        if (packed) { if (fast) MV_LAUNCH(true, true, true); else MV_LAUNCH(true, true, false); }
+        else        { if (fast) MV_LAUNCH(true, false, true); else MV_LAUNCH(true, false, false); }
     } else {
-        if (packed) hipLaunchKernelGGL((render_kernel<false, true>), grid, block, lds_bytes, stream, p);
-        else        hipLaunchKernelGGL((render_kernel<false, false>), grid, block, lds_bytes, stream, p);
+        if (packed) { if (fast) MV_LAUNCH(false, true, true); else MV_LAUNCH(false, true, false); }
+        else        { if (fast) MV_LAUNCH(false, false, true); else MV_LAUNCH(false, false, false); }
     }
+#undef MV_LAUNCH
     return hipGetLastError();
 }
 

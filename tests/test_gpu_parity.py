@@ -235,7 +235,8 @@ def _mini_spec(N, A, grid, W, H, M):
 
 
 @pytest.mark.parametrize("grid,W,H", [((7, 5, 3), 33, 19), ((1, 1, 1), 1, 1), ((8, 8, 4), 2, 2), ((5, 9, 2), 30, 17),
-                                      ((40, 40, 16), 130, 70), ((33, 2, 31), 64, 8)])
+                                      ((40, 40, 16), 130, 70), ((33, 2, 31), 64, 8), ((70, 9, 5), 40, 24),
+                                      ((64, 64, 6), 48, 32), ((9, 100, 4), 36, 20)])
 def test_unstructured_worlds_odd_sizes_cameras_anywhere(lib, orc, grid, W, H):
     """Random occupancy (overhangs, no floor), cameras inside, outside and inside solids, image sizes
     that are not multiples of the tile or of four, grids whose voxel count is not a multiple of 32."""
@@ -360,21 +361,32 @@ def _read_device(ptr, nbytes):
     return buf
 
 
-@pytest.mark.parametrize("grid", [(40, 40, 16), (7, 5, 3), (16, 16, 8)])
+@pytest.mark.parametrize("grid", [(40, 40, 16), (7, 5, 3), (16, 16, 8), (64, 64, 4), (70, 3, 5), (3, 130, 2)])
 def test_pack_kernel_bit_exact(lib, grid):
+    """Occupancy bit rows along x and along y, and the top solid layer, against NumPy."""
     rng = np.random.default_rng(17)
     N = 6
+    X, Y, Z = grid
     vox, pal = synth.random_world(rng, N, grid, 0.3, 4)
+    vox[3, Z // 2:] = 0                       # environment 3: empty upper half
+    vox[N - 1] = 0                            # last environment: empty
     batch = binding.Batch(N, 1, grid, 4, 16, 8)
     batch.upload_worlds(torch.from_numpy(vox).cuda(), torch.from_numpy(pal).cuda(), stream=_stream())
     torch.cuda.synchronize()
-    V = grid[0] * grid[1] * grid[2]
     for env in (0, 3, N - 1):
-        ptr, words = batch.debug_occupancy(env)
-        assert words == (V + 31) // 32
-        got = _read_device(ptr, words * 4)
-        want = np.packbits(np.pad(vox[env].reshape(-1) != 0, (0, words * 32 - V)), bitorder="little")
-        np.testing.assert_array_equal(got, want)
+        xp, xw, yp, yw, tp = batch.debug_occupancy(env)
+        assert xw == (X + 63) // 64 and yw == (Y + 63) // 64
+        occ = vox[env] != 0                                               # [Z,Y,X]
+        want_x = np.packbits(np.pad(occ, ((0, 0), (0, 0), (0, xw * 64 - X))), axis=-1, bitorder="little")
+        got_x = _read_device(xp, Z * Y * xw * 8).reshape(Z, Y, xw * 8)
+        np.testing.assert_array_equal(got_x, want_x)
+        occ_t = occ.transpose(0, 2, 1)                                    # [Z,X,Y]
+        want_y = np.packbits(np.pad(occ_t, ((0, 0), (0, 0), (0, yw * 64 - Y))), axis=-1, bitorder="little")
+        got_y = _read_device(yp, Z * X * yw * 8).reshape(Z, X, yw * 8)
+        np.testing.assert_array_equal(got_y, want_y)
+        layers = np.nonzero(occ.any(axis=(1, 2)))[0]
+        top = int(_read_device(tp, 4).view(np.int32)[0])
+        assert top == (int(layers.max()) + 1 if layers.size else 0)
 
 
 def test_camera_records_match_the_oracle(lib, orc):
