@@ -94,21 +94,33 @@ hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t 
 
 // ------------------------------------------------------------------------------------------
 // pack: one workgroup per environment.  Each wave takes whole z layers: the layer's material bytes
-// go through LDS (coalesced global reads, and the copy into the batch's own grid), then every bit
-// row is one wave ballot: lane = position along the row.
+// go through LDS (dword global reads, and the copy into the batch's own grid); then lane r builds
+// bit row r by walking along it (two vector operations per cell for 64 rows at once), first the
+// rows along x, then the rows along y, and the rows leave as one coalesced store per 64 rows.
 // ------------------------------------------------------------------------------------------
 constexpr int kPackThreads = 256;
 
+// Bits of `count` cells starting at `cell`, `stride` bytes apart: bit b = (cell[b*stride] != 0).
+__device__ __forceinline__ uint64_t gather_row_bits(const uint8_t* cell, int stride, int count)
+{
+    uint32_t lo = 0, hi = 0;
+    const int n_lo = min(count, 32);
+    for (int b = 0; b < n_lo; ++b, cell += stride) lo |= min((uint32_t)*cell, 1u) << b;
+    for (int b = 32; b < count; ++b, cell += stride) hi |= min((uint32_t)*cell, 1u) << (b - 32);
+    return ((uint64_t)hi << 32) | lo;
+}
+
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
                                                             uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
-                                                            GridLayout g)
+                                                            GridLayout g, int vec_ok)
 {
-    extern __shared__ uint8_t layer_lds[];                 // one layer per wave, padded to 16 bytes
+    extern __shared__ __align__(16) uint8_t layer_lds[];   // one layer per wave, padded to 16 bytes
     __shared__ int top_lds;
     const int env = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int waves = kPackThreads / 64;
-    const int XY = g.X * g.Y;
+    const int X = g.X, Y = g.Y;
+    const int XY = X * Y;
     const int layer_stride = (XY + 15) & ~15;
     uint8_t* mine = layer_lds + (size_t)wave * layer_stride;
     const size_t env_vox = (size_t)env * XY * g.Z;
@@ -121,31 +133,44 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
 
     for (int k = wave; k < g.Z; k += waves) {
         const uint8_t* lsrc = src + env_vox + (size_t)k * XY;
-        for (int b = lane; b < XY; b += 64) {
-            uint8_t m = lsrc[b];
-            mine[b] = m;
-            if (copy) vox_dst[env_vox + (size_t)k * XY + b] = m;
+        uint8_t* ldst = vox_dst + env_vox + (size_t)k * XY;
+        if (vec_ok) {
+            const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc);
+            uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
+            uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
+            for (int b = lane; b < (XY >> 2); b += 64) {
+                uint32_t v = s4[b];
+                m4[b] = v;
+                if (copy) d4[b] = v;
+            }
+        } else {
+            for (int b = lane; b < XY; b += 64) {
+                uint8_t m = lsrc[b];
+                mine[b] = m;
+                if (copy) ldst[b] = m;
+            }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        // x rows: row (k*Y + j), word w, bit = i - 64w
-        bool any = false;
-        for (int j = 0; j < g.Y; ++j)
+        uint64_t seen = 0;
+        // x rows: row (k*Y + j), word w holds cells i = 64w .. 64w+63
+        for (int j0 = 0; j0 < Y; j0 += 64) {
+            const int j = min(j0 + lane, Y - 1);
             for (int w = 0; w < g.rowwords_x; ++w) {
-                int i = w * 64 + lane;
-                bool s = i < g.X && mine[j * g.X + i] != 0;
-                uint64_t mask = __ballot(s);
-                any |= mask != 0;
-                if (lane == 0) xrows[((size_t)k * g.Y + j) * g.rowwords_x + w] = mask;
+                const uint64_t bits = gather_row_bits(mine + j * X + w * 64, 1, min(64, X - w * 64));
+                seen |= bits;
+                if (j0 + lane < Y) xrows[((size_t)k * Y + j) * g.rowwords_x + w] = bits;
             }
-        // y rows: row (k*X + i), word w, bit = j - 64w
-        for (int i = 0; i < g.X; ++i)
+        }
+        // y rows: row (k*X + i), word w holds cells j = 64w .. 64w+63
+        for (int i0 = 0; i0 < X; i0 += 64) {
+            const int i = min(i0 + lane, X - 1);
             for (int w = 0; w < g.rowwords_y; ++w) {
-                int j = w * 64 + lane;
-                bool s = j < g.Y && mine[j * g.X + i] != 0;
-                uint64_t mask = __ballot(s);
-                if (lane == 0) yrows[((size_t)k * g.X + i) * g.rowwords_y + w] = mask;
+                const uint64_t bits = gather_row_bits(mine + (w * 64) * X + i, X, min(64, Y - w * 64));
+                if (i0 + lane < X) yrows[((size_t)k * X + i) * g.rowwords_y + w] = bits;
             }
-        if (any) top = k + 1;
+        }
+        if (__ballot(seen != 0) != 0) top = k + 1;
         __builtin_amdgcn_wave_barrier();
     }
     if (lane == 0) atomicMax(&top_lds, top);
@@ -156,9 +181,13 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
 hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
                        const GridLayout& g, hipStream_t stream)
 {
-    size_t layer_stride = ((size_t)g.X * g.Y + 15) & ~(size_t)15;
-    size_t lds = layer_stride * (kPackThreads / 64);
-    hipLaunchKernelGGL(pack_kernel, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst, g);
+    const size_t XY = (size_t)g.X * g.Y;
+    const size_t layer_stride = (XY + 15) & ~(size_t)15;
+    const size_t lds = layer_stride * (kPackThreads / 64);
+    const int vec_ok = (XY % 4 == 0) && ((reinterpret_cast<uintptr_t>(src) & 3) == 0) &&
+                       ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
+    hipLaunchKernelGGL(pack_kernel, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst, g,
+                       vec_ok);
     return hipGetLastError();
 }
 
@@ -355,46 +384,72 @@ __device__ __forceinline__ Hit trace_generic(const uint32_t* __restrict__ xrows3
     return miss;
 }
 
-// Row-scan traversal: DDA over the (v,z) rows, one 64-bit shift per row.
-//   zc: uniform z constants {hi_z, lo_z, nz_pos, nz_neg} and k0
-__device__ __forceinline__ Hit trace_rows(const uint8_t* __restrict__ lds, uint32_t classes_off, float dx, float dy,
-                                          float dz, float hi_z, float lo_z, float nz_pos, float nz_neg, int k0, int X,
-                                          int Y, int max_steps)
+// One-instruction min/max: fminf()/fmaxf() make the compiler quiet possible signalling NaNs first
+// (an extra v_max per operand inside the loop); no operand here can be one.
+__device__ __forceinline__ float vmin(float a, float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+typedef __attribute__((address_space(3))) const uint64_t* lds_u64_ptr;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_ptr;
+
+// Row-scan traversal: DDA over the (v,z) rows the ray passes through, one 64-bit shift per row.
+// The loop has one exit (row holds a solid cell in range, or the ray leaves the grid).  It ends for
+// every input: each turn advances n_v or n_z, the crossing parameters n*dt + t0 never decrease, and
+// t_end is that same expression at the last plane of each axis, so t_out reaches t_end after at most
+// V + Z + 2 turns; a NaN anywhere makes the comparison false and ends it at once.
+__device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz, float hi_z, float lo_z,
+                                          float nz_pos, float nz_neg, int k0, int X, int Y)
 {
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
     const float dv = xm ? dy : dx;
     const int q = (xm ? 0 : 2) + (du < 0.0f ? 1 : 0);
-    const ScanClass c = *reinterpret_cast<const ScanClass*>(lds + classes_off + q * 64);
+    ScanClass c;
+    {
+        lds_u32x4_ptr rec = (lds_u32x4_ptr)(uintptr_t)(classes_addr + q * 64);
+        u32x4* dst = reinterpret_cast<u32x4*>(&c);
+        dst[0] = rec[0]; dst[1] = rec[1]; dst[2] = rec[2]; dst[3] = rec[3];
+    }
 
     const float dua = fabsf(du);
     const float inv_u = safe_rcp(dua);
     const float inv_v = safe_rcp(dv);
     const float inv_z = safe_rcp(dz);
     const float dt_v = fabsf(inv_v), dt_z = fabsf(inv_z);
+    const bool vneg = dv < 0.0f, zneg = dz < 0.0f;
     // first crossing on an axis: (upper plane - P)/d if d > 0, (lower plane - P)/d otherwise; the other
     // candidate is <= 0, so the maximum picks the right one without a compare
-    const float t0_v = fmaxf(c.hi_v * inv_v, c.lo_v * inv_v);
-    const float t0_z = fmaxf(hi_z * inv_z, lo_z * inv_z);
+    const float t0_v = vmax(c.hi_v * inv_v, c.lo_v * inv_v);
+    const float t0_z = vmax(hi_z * inv_z, lo_z * inv_z);
     // leaving the grid: same n*dt + t0 expression as the crossings, so the comparison below is exact
-    const float t_end = fminf(fminf(c.uexit * inv_u, fmaf(dv < 0.0f ? c.nv_neg : c.nv_pos, dt_v, t0_v)),
-                              fmaf(dz < 0.0f ? nz_neg : nz_pos, dt_z, t0_z));
-    const int sv = dv < 0.0f ? -8 : 8;
-    const int sz = dz < 0.0f ? -c.zstride : c.zstride;
+    const float t_end = vmin(vmin(c.uexit * inv_u, fmaf(vneg ? c.nv_neg : c.nv_pos, dt_v, t0_v)),
+                             fmaf(zneg ? nz_neg : nz_pos, dt_z, t0_z));
+    const int sv = vneg ? -8 : 8;
+    const int sz = zneg ? -c.zstride : c.zstride;
 
     float t_v = t0_v, t_z = t0_z, n_v = 0.0f, n_z = 0.0f;
-    int i_cur = c.i0, addr = c.addr0;
-    uint64_t r = 0;
-    bool found = false;
-    for (int it = 0; it < max_steps; ++it) {
-        const uint64_t row = *reinterpret_cast<const uint64_t*>(lds + addr);
-        const float t_out = fminf(t_v, t_z);
+    int i_cur = c.i0;
+    uint32_t addr = (uint32_t)c.addr0;
+    uint64_t r, in_range;
+    for (;;) {
+        const uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;
+        const float t_out = vmin(t_v, t_z);
         const float u_out = fmaf(t_out, dua, c.Pu);
         const int i_out = min((int)u_out, c.um1);
         r = row >> i_cur;                                   // drop the cells behind the ray
-        const uint64_t in_range = r << (63 - (i_out - i_cur));   // keep the cells up to where the ray leaves the row
-        if (in_range != 0) { found = true; break; }
-        if (!(t_out < t_end)) break;
+        in_range = r << (i_cur + 63 - i_out);               // keep the cells up to where the ray leaves the row
+        if ((in_range != 0) | !(t_out < t_end)) break;
         const bool cv = t_v <= t_z;
         const float one = cv ? 1.0f : 0.0f;
         n_v += one;
@@ -404,31 +459,32 @@ __device__ __forceinline__ Hit trace_rows(const uint8_t* __restrict__ lds, uint3
         t_z = fmaf(n_z, dt_z, t0_z);
         i_cur = i_out;
     }
-    if (!found) return Hit{ -1, 255, 0.0f };
+    const bool found = in_range != 0;
 
-    const int f = __builtin_ctzll(r);
+    const int f = __builtin_ctzll(r | (1ull << 63));
     const int iu = i_cur + f;                               // mirrored cell along u
     // the row was entered at the later of the last v crossing and the last z crossing (n-1; for n = 0
     // the expression is <= 0 because the first plane is at most one cell away)
     const float tv_last = fmaf(n_v - 1.0f, dt_v, t0_v);
     const float tz_last = fmaf(n_z - 1.0f, dt_z, t0_z);
     const bool via_z = tz_last >= tv_last;
-    const float t_in = fmaxf(fmaxf(tv_last, tz_last), 0.0f);
+    const float t_in = vmax(vmax(tv_last, tz_last), 0.0f);
     const bool started_here = (n_v + n_z) == 0.0f;
-    int face;
-    float t;
-    if (f != 0) {
-        face = c.face_u;
-        t = ((float)iu - c.Pu) * inv_u;
-    } else {
-        face = started_here ? 6 : (via_z ? 4 + (dz < 0.0f ? 1 : 0) : c.face_v + (dv < 0.0f ? 1 : 0));
-        t = t_in;
-    }
-    const int jv = c.j0 + (dv < 0.0f ? -(int)n_v : (int)n_v);
-    const int k = k0 + (dz < 0.0f ? -(int)n_z : (int)n_z);
+    const bool along_row = f != 0;
+    const float t_u = ((float)iu - c.Pu) * inv_u;
+    const int face_vz = via_z ? (zneg ? 5 : 4) : c.face_v + (vneg ? 1 : 0);
+    const int face = along_row ? c.face_u : (started_here ? 6 : face_vz);
+    const float t = along_row ? t_u : t_in;
+    const int jv = c.j0 + (vneg ? -1 : 1) * (int)n_v;
+    const int k = k0 + (zneg ? -1 : 1) * (int)n_z;
     const int io = c.mirror_a + c.mirror_b * iu;
-    const int idx = xm ? (k * Y + jv) * X + io : (k * Y + io) * X + jv;
-    return Hit{ idx, face, t };
+    const int jy = xm ? jv : io, ix = xm ? io : jv;
+    const int idx = (k * Y + jy) * X + ix;
+    Hit h;
+    h.idx = found ? idx : -1;
+    h.face = found ? face : 255;
+    h.t = found ? t : 0.0f;
+    return h;
 }
 
 template <bool AUX, bool PACKED, bool FAST>
@@ -436,6 +492,8 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
 {
     extern __shared__ __align__(16) uint8_t lds[];
     const int threads = p.threads;
+    // LDS byte address of the dynamic segment: row addresses in the scan-class records are absolute
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
 
     // XCD-aware mapping: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous range
     // of work items so that the blocks sharing an environment also share an L2.
@@ -532,7 +590,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         c.nv_neg = (float)c.j0;
         const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? g.xrow_words : 0)
                                                                    : 2 * g.xrow_words + (neg ? g.yrow_words : 0));
-        c.addr0 = (int)(array_off + 8u * (uint32_t)(k0 * V + c.j0));
+        c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(k0 * V + c.j0));
         c.zstride = 8 * V;
         c.um1 = U - 1;
         c.face_u = 2 * (xmaj ? 0 : 1) + (neg ? 1 : 0);
@@ -576,7 +634,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         // a5: traversal
         Hit h;
         if (FAST && origin_in_grid)
-            h = trace_rows(lds, off_classes, d[0], d[1], d[2], hi_z, lo_z, nz_pos, nz_neg, k0, X, Y, p.max_steps);
+            h = trace_rows(lds_base + off_classes, d[0], d[1], d[2], hi_z, lo_z, nz_pos, nz_neg, k0, X, Y);
         else
             h = trace_generic(reinterpret_cast<const uint32_t*>(lds_rows), 2 * g.rowwords_x, P, d, X, Y, Z,
                               origin_in_grid, p.max_steps);
