@@ -284,7 +284,6 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
     p.g = b->layout;
     p.voxels_per_env = b->voxels_per_env;
-    p.lut_in_lds = b->plan.lut_in_lds;
     p.threads = b->plan.threads;
     p.W = b->cfg.width; p.H = b->cfg.height; p.A = b->cfg.agents_per_env;
     p.materials_plus_one = b->materials_plus_one;

@@ -51,7 +51,6 @@ struct RenderParams {
     int32_t voxels_per_env;
     int32_t W, H, A;
     int32_t materials_plus_one;
-    int32_t lut_in_lds;                   // 1: the colour table of the environment is staged in LDS
     int32_t tiles_x, tiles_per_obs, tiles_per_block, blocks_per_obs;
     uint32_t total_blocks, blocks_per_xcd;
     uint32_t sky_packed;
@@ -65,7 +64,6 @@ GridLayout make_layout(int X, int Y, int Z);
 struct LdsPlan {
     size_t bytes;         // dynamic LDS per workgroup
     int    threads;       // workgroup size that keeps a CU busy with that much LDS
-    int    lut_in_lds;
 };
 LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one);
 

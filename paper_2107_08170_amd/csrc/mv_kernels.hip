@@ -36,21 +36,21 @@ GridLayout make_layout(int X, int Y, int Z)
 static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
 // LDS map (bytes):  [sx: W floats][sy: H floats] | [4 scan-class records, 64 B each] |
-//                   [colour table 7*(M+1) dwords, optional] | bit rows
+//                   [colour table 7*(M+1) dwords] | bit rows
 // fast grids stage four row arrays (x, x mirrored, y, y mirrored); others stage the x rows only.
 struct LdsMap {
     uint32_t scalars, classes, lut, rows;
     uint32_t total;
 };
 
-static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one, bool lut_in_lds)
+static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one)
 {
     LdsMap m{};
     size_t off = 0;
     m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
     m.classes = (uint32_t)off; off += 4 * 64;
     m.lut = (uint32_t)off;
-    if (lut_in_lds) off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
+    off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
     m.rows = (uint32_t)off;
     off += g.fast ? 2 * (size_t)g.env_words * 8 : (size_t)g.xrow_words * 8;
     m.total = (uint32_t)off;
@@ -61,13 +61,9 @@ LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one)
 {
     LdsPlan plan{};
     size_t rows = g.fast ? 2 * (size_t)g.env_words * 8 : (size_t)g.xrow_words * 8;
-    if (rows + (size_t)(W + H) * 4 + 1024 > kLdsBudget) return plan;       // bytes == 0: does not fit
-    plan.lut_in_lds = 1;
-    LdsMap m = lds_map(g, W, H, materials_plus_one, true);
-    if (m.total > kLdsBudget) {
-        plan.lut_in_lds = 0;
-        m = lds_map(g, W, H, materials_plus_one, false);
-    }
+    (void)rows;
+    const LdsMap m = lds_map(g, W, H, materials_plus_one);
+    if (m.total > kLdsBudget) return plan;                                  // bytes == 0: does not fit
     plan.bytes = m.total;
     // keep at least ~16 waves resident per CU whatever one workgroup's LDS share is
     size_t per_cu = kLdsBudget / plan.bytes;
@@ -105,8 +101,11 @@ __device__ __forceinline__ uint64_t gather_row_bits(const uint8_t* cell, int str
 {
     uint32_t lo = 0, hi = 0;
     const int n_lo = min(count, 32);
-    for (int b = 0; b < n_lo; ++b, cell += stride) lo |= min((uint32_t)*cell, 1u) << b;
-    for (int b = 32; b < count; ++b, cell += stride) hi |= min((uint32_t)*cell, 1u) << (b - 32);
+    // unrolled so that the LDS reads of several cells are in flight together
+#pragma unroll 8
+    for (int b = 0; b < n_lo; ++b) lo |= min((uint32_t)cell[b * stride], 1u) << b;
+#pragma unroll 8
+    for (int b = 32; b < count; ++b) hi |= min((uint32_t)cell[b * stride], 1u) << (b - 32);
     return ((uint64_t)hi << 32) | lo;
 }
 
@@ -138,10 +137,22 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
             const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc);
             uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
             uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
-            for (int b = lane; b < (XY >> 2); b += 64) {
-                uint32_t v = s4[b];
-                m4[b] = v;
-                if (copy) d4[b] = v;
+            const int n4 = XY >> 2;
+            for (int b0 = 0; b0 < n4; b0 += 8 * 64) {       // eight loads in flight per lane
+                uint32_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int b = b0 + u * 64 + lane;
+                    v[u] = b < n4 ? s4[b] : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int b = b0 + u * 64 + lane;
+                    if (b < n4) {
+                        m4[b] = v[u];
+                        if (copy) d4[b] = v[u];
+                    }
+                }
             }
         } else {
             for (int b = lane; b < XY; b += 64) {
@@ -403,11 +414,14 @@ typedef __attribute__((address_space(3))) const uint64_t* lds_u64_ptr;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_ptr;
 
+__device__ __forceinline__ int mad24(int a, int b, int c) { return __mul24(a, b) + c; }   // v_mad_i32_i24
+
 // Row-scan traversal: DDA over the (v,z) rows the ray passes through, one 64-bit shift per row.
 // The loop has one exit (row holds a solid cell in range, or the ray leaves the grid).  It ends for
-// every input: each turn advances n_v or n_z, the crossing parameters n*dt + t0 never decrease, and
+// every input: each turn advances n_v or n_z, the crossing parameters |n|*dt + t0 never decrease, and
 // t_end is that same expression at the last plane of each axis, so t_out reaches t_end after at most
 // V + Z + 2 turns; a NaN anywhere makes the comparison false and ends it at once.
+// n_v and n_z count crossings with the sign of the direction, so that the cell is j0 + n_v, k0 + n_z.
 __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz, float hi_z, float lo_z,
                                           float nz_pos, float nz_neg, int k0, int X, int Y)
 {
@@ -432,11 +446,12 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     // candidate is <= 0, so the maximum picks the right one without a compare
     const float t0_v = vmax(c.hi_v * inv_v, c.lo_v * inv_v);
     const float t0_z = vmax(hi_z * inv_z, lo_z * inv_z);
-    // leaving the grid: same n*dt + t0 expression as the crossings, so the comparison below is exact
+    // leaving the grid: same |n|*dt + t0 expression as the crossings, so the comparison below is exact
     const float t_end = vmin(vmin(c.uexit * inv_u, fmaf(vneg ? c.nv_neg : c.nv_pos, dt_v, t0_v)),
                              fmaf(zneg ? nz_neg : nz_pos, dt_z, t0_z));
     const int sv = vneg ? -8 : 8;
     const int sz = zneg ? -c.zstride : c.zstride;
+    const float step_v = vneg ? -1.0f : 1.0f, step_z = zneg ? -1.0f : 1.0f;
 
     float t_v = t0_v, t_z = t0_z, n_v = 0.0f, n_z = 0.0f;
     int i_cur = c.i0;
@@ -451,40 +466,46 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
         in_range = r << (i_cur + 63 - i_out);               // keep the cells up to where the ray leaves the row
         if ((in_range != 0) | !(t_out < t_end)) break;
         const bool cv = t_v <= t_z;
-        const float one = cv ? 1.0f : 0.0f;
-        n_v += one;
-        n_z += 1.0f - one;
+        n_v += cv ? step_v : 0.0f;
+        n_z += cv ? 0.0f : step_z;
         addr += cv ? sv : sz;
-        t_v = fmaf(n_v, dt_v, t0_v);
-        t_z = fmaf(n_z, dt_z, t0_z);
+        t_v = fmaf(fabsf(n_v), dt_v, t0_v);
+        t_z = fmaf(fabsf(n_z), dt_z, t0_z);
         i_cur = i_out;
     }
     const bool found = in_range != 0;
 
     const int f = __builtin_ctzll(r | (1ull << 63));
     const int iu = i_cur + f;                               // mirrored cell along u
-    // the row was entered at the later of the last v crossing and the last z crossing (n-1; for n = 0
+    // the row was entered at the later of the last v crossing and the last z crossing (|n|-1; for n = 0
     // the expression is <= 0 because the first plane is at most one cell away)
-    const float tv_last = fmaf(n_v - 1.0f, dt_v, t0_v);
-    const float tz_last = fmaf(n_z - 1.0f, dt_z, t0_z);
+    const float tv_last = fmaf(fabsf(n_v) - 1.0f, dt_v, t0_v);
+    const float tz_last = fmaf(fabsf(n_z) - 1.0f, dt_z, t0_z);
     const bool via_z = tz_last >= tv_last;
     const float t_in = vmax(vmax(tv_last, tz_last), 0.0f);
-    const bool started_here = (n_v + n_z) == 0.0f;
+    const bool started_here = (__float_as_uint(n_v) | __float_as_uint(n_z)) == 0u;
     const bool along_row = f != 0;
     const float t_u = ((float)iu - c.Pu) * inv_u;
     const int face_vz = via_z ? (zneg ? 5 : 4) : c.face_v + (vneg ? 1 : 0);
     const int face = along_row ? c.face_u : (started_here ? 6 : face_vz);
     const float t = along_row ? t_u : t_in;
-    const int jv = c.j0 + (vneg ? -1 : 1) * (int)n_v;
-    const int k = k0 + (zneg ? -1 : 1) * (int)n_z;
-    const int io = c.mirror_a + c.mirror_b * iu;
+    const int jv = c.j0 + (int)n_v;
+    const int k = k0 + (int)n_z;
+    const int io = mad24(c.mirror_b, iu, c.mirror_a);
     const int jy = xm ? jv : io, ix = xm ? io : jv;
-    const int idx = (k * Y + jy) * X + ix;
+    const int idx = mad24(mad24(k, Y, jy), X, ix);
     Hit h;
     h.idx = found ? idx : -1;
     h.face = found ? face : 255;
     h.t = found ? t : 0.0f;
     return h;
+}
+
+// colour of lane+1 within each group of four lanes (lane 3 of the group keeps its own): DPP
+// quad_perm [1,2,3,3]
+__device__ __forceinline__ uint32_t next_in_quad(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xF9, 0xF, 0xF, false);
 }
 
 template <bool AUX, bool PACKED, bool FAST>
@@ -510,23 +531,25 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     const uint32_t off_scalars = 0;
     const uint32_t off_classes = (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
     const uint32_t off_lut = off_classes + 256;
-    const uint32_t off_rows = off_lut + (p.lut_in_lds ? (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15) : 0u);
+    const uint32_t off_rows = off_lut + (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15);
     float* lds_sx = reinterpret_cast<float*>(lds + off_scalars);
     float* lds_sy = lds_sx + p.W;
     uint64_t* lds_rows = reinterpret_cast<uint64_t*>(lds + off_rows);
 
-    const CameraRecord& rec = p.rec[obs];
-    const float P[3] = { rec.P[0], rec.P[1], rec.P[2] };
-    const int self_lo = rec.self_lo;
+    // the camera: uniform for the whole workgroup, read once
+    const CameraRecord* __restrict__ recp = p.rec + obs;
+    const float P[3] = { recp->P[0], recp->P[1], recp->P[2] };
+    const float Fx = recp->F[0], Fy = recp->F[1], Fz = recp->F[2];
+    const float Rx = recp->R[0], Ry = recp->R[1], Rz = recp->R[2];
+    const float Ux = recp->U[0], Uy = recp->U[1], Uz = recp->U[2];
+    const int self_lo = recp->self_lo, self_hi = recp->self_hi;
 
     {   // a3: stage pixel scalars, colour table and this environment's bit rows
         for (int i = threadIdx.x; i < p.W; i += threads) lds_sx[i] = p.sx[i];
         for (int i = threadIdx.x; i < p.H; i += threads) lds_sy[i] = p.sy[i];
-        if (p.lut_in_lds) {
-            const uint32_t* gl = p.lut + (size_t)env * kNumFaces * p.materials_plus_one;
-            uint32_t* ll = reinterpret_cast<uint32_t*>(lds + off_lut);
-            for (int i = threadIdx.x; i < kNumFaces * p.materials_plus_one; i += threads) ll[i] = gl[i];
-        }
+        const uint32_t* gl = p.lut + (size_t)env * kNumFaces * p.materials_plus_one;
+        uint32_t* ll = reinterpret_cast<uint32_t*>(lds + off_lut);
+        for (int i = threadIdx.x; i < kNumFaces * p.materials_plus_one; i += threads) ll[i] = gl[i];
         const uint64_t* gb = p.bits + (size_t)env * g.env_words;
         if (FAST) {
             // arrays: [x rows][x rows mirrored][y rows][y rows mirrored]
@@ -557,7 +580,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     // This workgroup's copy of the rows is private to one camera: remove the camera's own body from it
     // once, instead of testing for it at every step.
     if (self_lo >= 0 && threadIdx.x < 2) {
-        int s = threadIdx.x == 0 ? self_lo : rec.self_hi;
+        int s = threadIdx.x == 0 ? self_lo : self_hi;
         if (s >= 0 && s < X * Y * Z) {
             int k = s / (X * Y), rem = s - k * X * Y, j = rem / X, i = rem - j * X;
             if (FAST) {
@@ -612,24 +635,33 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int waves = threads >> 6;
     const int lane = threadIdx.x & 63;
+    const int lx = lane & 7, ly = lane >> 3, quad = lane & 3;
     const int tile_begin = part * p.tiles_per_block;
     const int tile_end = min(tile_begin + p.tiles_per_block, p.tiles_per_obs);
+    // per-observation bases: everything inside one observation is addressed with 32-bit offsets
     const size_t obs_pix = (size_t)obs * p.H * p.W;
-    const uint8_t* vox_env = p.vox + (size_t)env * p.voxels_per_env;
-    const uint32_t* lut_env = p.lut + (size_t)env * kNumFaces * p.materials_plus_one;
+    float* __restrict__ depth_obs = p.depth + obs_pix;
+    uint8_t* __restrict__ rgb_obs = p.rgb + obs_pix * 3;
+    uint8_t* __restrict__ auxm_obs = AUX && p.aux_material ? p.aux_material + obs_pix : nullptr;
+    int32_t* __restrict__ auxh_obs = AUX && p.aux_hit ? p.aux_hit + obs_pix : nullptr;
+    uint8_t* __restrict__ auxf_obs = AUX && p.aux_face ? p.aux_face + obs_pix : nullptr;
+    const uint8_t* __restrict__ vox_env = p.vox + (size_t)env * p.voxels_per_env;
     const uint32_t* lut_lds = reinterpret_cast<const uint32_t*>(lds + off_lut);
+    const uint32_t last_voxel = (uint32_t)p.voxels_per_env - 1u;
+    const int last_material = p.materials_plus_one - 1;
 
     for (int tile = tile_begin + wave; tile < tile_end; tile += waves) {
         const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
-        const int col = tx * kTile + (lane & 7), row = ty * kTile + (lane >> 3);
+        const int col = tx * kTile + lx, row = ty * kTile + ly;
         const bool active = col < p.W && row < p.H;
         const int ccol = min(col, p.W - 1), crow = min(row, p.H - 1);
 
         // a4: ray through the pixel centre, two fused multiply-adds per axis
         const float sx = lds_sx[ccol], sy = lds_sy[crow];
         float d[3];
-#pragma unroll
-        for (int a = 0; a < 3; ++a) d[a] = fmaf(sy, rec.U[a], fmaf(sx, rec.R[a], rec.F[a]));
+        d[0] = fmaf(sy, Ux, fmaf(sx, Rx, Fx));
+        d[1] = fmaf(sy, Uy, fmaf(sx, Ry, Fy));
+        d[2] = fmaf(sy, Uz, fmaf(sx, Rz, Fz));
 
         // a5: traversal
         Hit h;
@@ -643,35 +675,30 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         uint32_t colour = p.sky_packed;
         int material = 0;
         if (h.idx >= 0) {
-            const int safe_idx = min(h.idx, p.voxels_per_env - 1);
-            material = vox_env[safe_idx];
-            const int m = min(material, p.materials_plus_one - 1);
-            const int li = h.face * p.materials_plus_one + m;
-            colour = p.lut_in_lds ? lut_lds[li] : lut_env[li];
+            material = vox_env[min((uint32_t)h.idx, last_voxel)];
+            colour = lut_lds[mad24(h.face, p.materials_plus_one, min(material, last_material))];
         }
 
         // a7: stores
-        const size_t pix = obs_pix + (size_t)crow * p.W + ccol;
+        const uint32_t pix = (uint32_t)mad24(crow, p.W, ccol);
         if (active) {
-            p.depth[pix] = h.t;
+            depth_obs[pix] = h.t;
             if (AUX) {
-                if (p.aux_material) p.aux_material[pix] = (uint8_t)material;
-                if (p.aux_hit) p.aux_hit[pix] = h.idx;
-                if (p.aux_face) p.aux_face[pix] = (uint8_t)h.face;
+                if (auxm_obs) auxm_obs[pix] = (uint8_t)material;
+                if (auxh_obs) auxh_obs[pix] = h.idx;
+                if (auxf_obs) auxf_obs[pix] = (uint8_t)h.face;
             }
         }
         if (PACKED) {
             // W % 4 == 0: four consecutive lanes hold four consecutive pixels of one row = 12 bytes =
-            // three aligned dwords, written by the first three lanes of the quad.
-            const uint32_t next = __shfl_down(colour, 1);
-            const int m = lane & 3;
-            const uint32_t word = (colour >> (8 * m)) | (next << (24 - 8 * m));
-            if (active && m < 3) {
-                uint32_t* out = reinterpret_cast<uint32_t*>(p.rgb + (pix - m) * 3) + m;
-                *out = word;
-            }
+            // three aligned dwords, written by the first three lanes of the quad: dword m holds the
+            // upper 4-m bytes' worth of pixel m and the lower m+1 bytes of pixel m+1.
+            const uint32_t next = next_in_quad(colour);
+            const uint32_t word = (colour >> (8 * quad)) | (next << (24 - 8 * quad));
+            if (active && quad < 3)
+                *reinterpret_cast<uint32_t*>(rgb_obs + (3u * pix + (uint32_t)quad)) = word;
         } else if (active) {
-            uint8_t* out = p.rgb + pix * 3;
+            uint8_t* out = rgb_obs + 3u * pix;
             out[0] = (uint8_t)colour;
             out[1] = (uint8_t)(colour >> 8);
             out[2] = (uint8_t)(colour >> 16);
