@@ -21,6 +21,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E datasheet peak
+# Plain vector-ALU issue ceiling: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one lane-instruction per lane
+# and clock (the published 157.3 TFLOP/s fp32 vector figure counts an FMA as 2 and packed issue as 2).
+ALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # 39321.6 G lane-instructions/s
+# Mean per-cell DDA steps per ray of the CPU oracle on camera set 0 of each workload (measured with the
+# oracle's step counter on the first 256/512/256/128 environments); the cpu_baseline leg re-measures it.
+ORACLE_MEAN_STEPS = {1: 8.75, 2: 8.98, 3: 8.45, 4: 10.20}
+
+
+def algorithmic_lane_ops_per_ray(mean_steps: float) -> float:
+    """ALU work a plain per-cell DDA ray caster needs per ray: 13 lane-instructions per step (select the
+    nearest plane, advance, recompute its crossing, test one bit) plus 80 fixed (ray set-up with three
+    reciprocals, hit point, shading, stores)."""
+    return 13.0 * mean_steps + 80.0
 
 
 def algorithmic_bytes_per_obs(spec) -> float:
@@ -34,6 +47,21 @@ def algorithmic_bytes_per_obs(spec) -> float:
     return rays * 7 + rays * 1 + (occ_bytes + lut_bytes) / spec.agents_per_env + 64
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per render launch from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE
+    scaled against a plain copy), or None when no summary covers this workload."""
+    path = os.path.join(ROOT, "profiles", "render_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 2 and parts[0] == workload:
+                    return float(parts[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +73,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample-envs", type=int, default=4096)
     ap.add_argument("--static-worlds", action="store_true",
                     help="upload the worlds once instead of every step (not the headline number)")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy five times, for scaling the HBM byte "
+                         "counters of a rocprofv3 --pmc run against a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (environments are independent; "
@@ -59,6 +90,16 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+    if args.traffic_calibration:
+        nbytes = 1 << 30
+        src = torch.full((nbytes,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read": nbytes, "bytes_written": nbytes, "repeats": 5}))
+        return 0
     mv.load_library()
 
     spec = synth.SPECS[args.config]
@@ -150,11 +191,21 @@ def main() -> int:
         "render_kernel_ms": {"mean": float(render_ms.mean()), "median": float(np.median(render_ms)),
                              "p95": float(np.percentile(render_ms, 95))},
         "render_only_obs_per_s": n / (render_ms.mean() * 1e-3),
-        "roofline": {"bound": "hbm", "kernel": "mv::render_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": alg_bytes},
         "generator_seconds": gen_s,
     }
+    traffic = measured_traffic(spec.name)
+    mean_steps = ORACLE_MEAN_STEPS.get(args.config)
+    alg_ops = algorithmic_lane_ops_per_ray(mean_steps) * rays_per_obs * n if mean_steps else None
+    if alg_ops is not None:
+        alu_achieved = alg_ops / (render_ms.mean() * 1e-3) / 1e9
+        # the render kernel issues vector instructions 95 % of the time: plain ALU arithmetic binds it
+        result["roofline"] = {"bound": "alu", "kernel": "mv::render_kernel", "achieved": alu_achieved,
+                              "peak": ALU_PEAK_GOPS, "unit": "G lane-instructions/s",
+                              "frac": alu_achieved / ALU_PEAK_GOPS, "traffic": traffic,
+                              "algorithmic_ops_per_launch": alg_ops, "oracle_mean_steps_per_ray": mean_steps}
+    result["hbm_roofline"] = {"bound": "hbm", "kernel": "mv::render_kernel", "achieved": achieved,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                              "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes}
 
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
@@ -167,10 +218,12 @@ def main() -> int:
         t0 = time.perf_counter()
         ob.render(threads=cores, side_channels=False)
         cpu_s = time.perf_counter() - t0
+        steps_sample = ob.render(first_obs=0, count=min(64, envs * spec.agents_per_env), threads=cores).steps
         result["cpu_baseline"] = {"value": envs * spec.agents_per_env / cpu_s, "unit": "observations/s",
                                   "cores": cores, "kind": "oracle",
                                   "sample": f"first {envs} environments ({envs * spec.agents_per_env} observations) "
-                                            f"of camera set 0, {cpu_s:.2f} s wall"}
+                                            f"of camera set 0, {cpu_s:.2f} s wall",
+                                  "mean_dda_steps_per_ray": float(steps_sample.mean())}
     print(json.dumps(result))
     return 0
 

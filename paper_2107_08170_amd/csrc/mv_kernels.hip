@@ -96,6 +96,15 @@ hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t 
 // ------------------------------------------------------------------------------------------
 constexpr int kPackThreads = 256;
 
+// 1 if the byte is non-zero (one v_min_u32; written as asm because the compiler otherwise expands the
+// idiom into a compare and a select)
+__device__ __forceinline__ uint32_t nonzero(uint32_t byte)
+{
+    uint32_t r;
+    asm("v_min_u32 %0, 1, %1" : "=v"(r) : "v"(byte));
+    return r;
+}
+
 // Bits of `count` cells starting at `cell`, `stride` bytes apart: bit b = (cell[b*stride] != 0).
 __device__ __forceinline__ uint64_t gather_row_bits(const uint8_t* cell, int stride, int count)
 {
@@ -103,11 +112,13 @@ __device__ __forceinline__ uint64_t gather_row_bits(const uint8_t* cell, int str
     const int n_lo = min(count, 32);
     // unrolled so that the LDS reads of several cells are in flight together
 #pragma unroll 8
-    for (int b = 0; b < n_lo; ++b) lo |= min((uint32_t)cell[b * stride], 1u) << b;
+    for (int b = 0; b < n_lo; ++b) lo |= nonzero(cell[b * stride]) << b;
 #pragma unroll 8
-    for (int b = 32; b < count; ++b) hi |= min((uint32_t)cell[b * stride], 1u) << (b - 32);
+    for (int b = 32; b < count; ++b) hi |= nonzero(cell[b * stride]) << (b - 32);
     return ((uint64_t)hi << 32) | lo;
 }
+
+constexpr int kPackPrefetch = 8;           // dwords of the next layer each lane keeps in flight
 
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
                                                             uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
@@ -129,30 +140,44 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     if (threadIdx.x == 0) top_lds = 0;
     __syncthreads();
     int top = 0;
+    // a layer of up to 8*64 dwords (2 KiB) is prefetched into registers while the previous one is packed
+    const int n4 = XY >> 2;
+    const bool prefetch = vec_ok && n4 <= kPackPrefetch * 64;
+    const bool quick = g.fast && (X & 3) == 0 && XY >= 8 * Y;     // the x rows (8 B each) fit over the layer in LDS
+    uint32_t pre[kPackPrefetch];
+    if (prefetch && wave < g.Z) {
+        const uint32_t* s4 = reinterpret_cast<const uint32_t*>(src + env_vox + (size_t)wave * XY);
+#pragma unroll
+        for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? s4[u * 64 + lane] : 0u;
+    }
 
     for (int k = wave; k < g.Z; k += waves) {
         const uint8_t* lsrc = src + env_vox + (size_t)k * XY;
         uint8_t* ldst = vox_dst + env_vox + (size_t)k * XY;
-        if (vec_ok) {
+        if (prefetch) {
+            uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
+            uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
+#pragma unroll
+            for (int u = 0; u < kPackPrefetch; ++u) {
+                const int b = u * 64 + lane;
+                if (b < n4) {
+                    m4[b] = pre[u];
+                    if (copy) d4[b] = pre[u];
+                }
+            }
+            if (k + waves < g.Z) {
+                const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc + (size_t)waves * XY);
+#pragma unroll
+                for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? s4[u * 64 + lane] : 0u;
+            }
+        } else if (vec_ok) {
             const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc);
             uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
             uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
-            const int n4 = XY >> 2;
-            for (int b0 = 0; b0 < n4; b0 += 8 * 64) {       // eight loads in flight per lane
-                uint32_t v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int b = b0 + u * 64 + lane;
-                    v[u] = b < n4 ? s4[b] : 0u;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int b = b0 + u * 64 + lane;
-                    if (b < n4) {
-                        m4[b] = v[u];
-                        if (copy) d4[b] = v[u];
-                    }
-                }
+            for (int b = lane; b < n4; b += 64) {
+                uint32_t v = s4[b];
+                m4[b] = v;
+                if (copy) d4[b] = v;
             }
         } else {
             for (int b = lane; b < XY; b += 64) {
@@ -164,6 +189,39 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         uint64_t seen = 0;
+        if (quick) {
+            // One word per row, X a multiple of 4.  x rows: lane j reads its row as dwords; the non-zero
+            // bytes of a dword become a nibble (carry trick + one dot product with weights 1,2,4,8).
+            uint32_t lo = 0, hi = 0;
+            const uint32_t* rowp = reinterpret_cast<const uint32_t*>(mine + min(lane, Y - 1) * X);
+#pragma unroll
+            for (int w4 = 0; w4 < 16; ++w4) {
+                if (w4 * 4 < X) {
+                    const uint32_t x = rowp[w4];
+                    const uint32_t flags = ((((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) >> 7) & 0x01010101u;
+                    const uint32_t nib = __builtin_amdgcn_udot4(flags, 0x08040201u, 0u, false);
+                    if (w4 < 8) lo |= nib << (4 * w4); else hi |= nib << (4 * (w4 - 8));
+                }
+            }
+            const uint64_t xbits = ((uint64_t)hi << 32) | lo;
+            seen = xbits;
+            if (lane < Y) xrows[(size_t)k * Y + lane] = xbits;
+            // y rows = the transpose of the x-row bit matrix: the x rows go to LDS (over the layer's first
+            // bytes, which every lane has finished reading), then lane i collects bit i of every row j
+            // from broadcast reads.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            uint64_t* xr = reinterpret_cast<uint64_t*>(mine);
+            if (lane < Y) xr[lane] = xbits;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            uint32_t ylo = 0, yhi = 0;
+#pragma unroll 8
+            for (int j = 0; j < min(Y, 32); ++j) ylo |= ((uint32_t)(xr[j] >> lane) & 1u) << j;
+#pragma unroll 8
+            for (int j = 32; j < Y; ++j) yhi |= ((uint32_t)(xr[j] >> lane) & 1u) << (j - 32);
+            if (lane < X) yrows[(size_t)k * X + lane] = ((uint64_t)yhi << 32) | ylo;
+        } else {
         // x rows: row (k*Y + j), word w holds cells i = 64w .. 64w+63
         for (int j0 = 0; j0 < Y; j0 += 64) {
             const int j = min(j0 + lane, Y - 1);
@@ -180,6 +238,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
                 const uint64_t bits = gather_row_bits(mine + (w * 64) * X + i, X, min(64, Y - w * 64));
                 if (i0 + lane < X) yrows[((size_t)k * X + i) * g.rowwords_y + w] = bits;
             }
+        }
         }
         if (__ballot(seen != 0) != 0) top = k + 1;
         __builtin_amdgcn_wave_barrier();
