@@ -473,7 +473,13 @@ typedef __attribute__((address_space(3))) const uint64_t* lds_u64_ptr;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_ptr;
 
-__device__ __forceinline__ int mad24(int a, int b, int c) { return __mul24(a, b) + c; }   // v_mad_i32_i24
+// a*b + c on the 24-bit multiplier (full rate); every product on this path fits 24 x 24 bits
+__device__ __forceinline__ int mad24(int a, int b, int c)
+{
+    int r;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 
 // Row-scan traversal: DDA over the (v,z) rows the ray passes through, one 64-bit shift per row.
 // The loop has one exit (row holds a solid cell in range, or the ray leaves the grid).  It ends for
@@ -513,29 +519,41 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const float step_v = vneg ? -1.0f : 1.0f, step_z = zneg ? -1.0f : 1.0f;
 
     float t_v = t0_v, t_z = t0_z, n_v = 0.0f, n_z = 0.0f;
-    int i_cur = c.i0;
     uint32_t addr = (uint32_t)c.addr0;
     uint64_t r, in_range;
-    for (;;) {
-        const uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;
-        const float t_out = vmin(t_v, t_z);
-        const float u_out = fmaf(t_out, dua, c.Pu);
-        const int i_out = min((int)u_out, c.um1);
-        r = row >> i_cur;                                   // drop the cells behind the ray
-        in_range = r << (i_cur + 63 - i_out);               // keep the cells up to where the ray leaves the row
-        if ((in_range != 0) | !(t_out < t_end)) break;
-        const bool cv = t_v <= t_z;
-        n_v += cv ? step_v : 0.0f;
-        n_z += cv ? 0.0f : step_z;
-        addr += cv ? sv : sz;
-        t_v = fmaf(fabsf(n_v), dt_v, t0_v);
-        t_z = fmaf(fabsf(n_z), dt_z, t0_z);
-        i_cur = i_out;
+    int i_last;
+    // One turn of the loop scans the current row from cell i_from up to the cell i_to where the ray leaves
+    // it.  The second shift count is 63 - (i_to - i_from) = (i_from + ~i_to) mod 64: one xor-add, the
+    // shifter ignores the upper bits.  Nothing after the loop needs i_from: the hit cell follows from
+    // the lowest set bit of in_range and i_to, and bit 0 of r tells whether it is the row's entry cell.
+#define MV_ROW_TURN(i_from, i_to)                                                             \
+    {                                                                                         \
+        const uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;                                   \
+        const float t_out = vmin(t_v, t_z);                                                   \
+        const float u_out = fmaf(t_out, dua, c.Pu);                                           \
+        i_to = min((int)u_out, c.um1);                                                        \
+        r = row >> (i_from);                                                                  \
+        in_range = r << ((((i_to) ^ -1) + (i_from)) & 63);                                    \
+        i_last = i_to;                                                                        \
+        if ((in_range != 0) | !(t_out < t_end)) break;                                        \
+        const bool cv = t_v <= t_z;                                                           \
+        n_v += cv ? step_v : 0.0f;                                                            \
+        n_z += cv ? 0.0f : step_z;                                                            \
+        addr += cv ? sv : sz;                                                                 \
+        t_v = fmaf(fabsf(n_v), dt_v, t0_v);                                                   \
+        t_z = fmaf(fabsf(n_z), dt_z, t0_z);                                                   \
     }
+    int i_a = c.i0, i_b;
+    for (;;) {                                  // two turns per trip: the cell index alternates registers
+        MV_ROW_TURN(i_a, i_b)
+        MV_ROW_TURN(i_b, i_a)
+    }
+#undef MV_ROW_TURN
     const bool found = in_range != 0;
 
-    const int f = __builtin_ctzll(r | (1ull << 63));
-    const int iu = i_cur + f;                               // mirrored cell along u
+    // in_range is r moved up so that cell i_last sits at bit 63: its lowest set bit p is cell i_last - (63 - p)
+    const int iu = i_last - 63 + __builtin_ctzll(in_range | (1ull << 63));      // mirrored cell along u
+    const bool along_row = ((uint32_t)r & 1u) == 0u;                            // not the row's entry cell
     // the row was entered at the later of the last v crossing and the last z crossing (|n|-1; for n = 0
     // the expression is <= 0 because the first plane is at most one cell away)
     const float tv_last = fmaf(fabsf(n_v) - 1.0f, dt_v, t0_v);
@@ -543,7 +561,6 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const bool via_z = tz_last >= tv_last;
     const float t_in = vmax(vmax(tv_last, tz_last), 0.0f);
     const bool started_here = (__float_as_uint(n_v) | __float_as_uint(n_z)) == 0u;
-    const bool along_row = f != 0;
     const float t_u = ((float)iu - c.Pu) * inv_u;
     const int face_vz = via_z ? (zneg ? 5 : 4) : c.face_v + (vneg ? 1 : 0);
     const int face = along_row ? c.face_u : (started_here ? 6 : face_vz);
