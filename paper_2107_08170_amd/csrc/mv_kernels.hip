@@ -571,9 +571,9 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const int jy = xm ? jv : io, ix = xm ? io : jv;
     const int idx = mad24(mad24(k, Y, jy), X, ix);
     Hit h;
-    h.idx = found ? idx : -1;
-    h.face = found ? face : 255;
-    h.t = found ? t : 0.0f;
+    h.idx = found ? idx : -1;       // face and t are only meaningful for idx >= 0; the caller substitutes the miss values
+    h.face = face;
+    h.t = t;
     return h;
 }
 
@@ -729,8 +729,9 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     for (int tile = tile_begin + wave; tile < tile_end; tile += waves) {
         const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
         const int col = tx * kTile + lx, row = ty * kTile + ly;
-        const bool active = col < p.W && row < p.H;
-        const int ccol = min(col, p.W - 1), crow = min(row, p.H - 1);
+        // PACKED launches have W and H multiples of the tile size: every lane owns a pixel
+        const bool active = PACKED ? true : (col < p.W && row < p.H);
+        const int ccol = PACKED ? col : min(col, p.W - 1), crow = PACKED ? row : min(row, p.H - 1);
 
         // a4: ray through the pixel centre, two fused multiply-adds per axis
         const float sx = lds_sx[ccol], sy = lds_sy[crow];
@@ -748,31 +749,35 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
                               origin_in_grid, p.max_steps);
 
         // a6: shade
+        const bool hit = h.idx >= 0;
         uint32_t colour = p.sky_packed;
-        int material = 0;
-        if (h.idx >= 0) {
+        float depth = 0.0f;
+        int material = 0, face = 255;
+        if (hit) {
             material = vox_env[min((uint32_t)h.idx, last_voxel)];
             colour = lut_lds[mad24(h.face, p.materials_plus_one, min(material, last_material))];
+            depth = h.t;
+            face = h.face;
         }
 
         // a7: stores
         const uint32_t pix = (uint32_t)mad24(crow, p.W, ccol);
         if (active) {
-            depth_obs[pix] = h.t;
+            depth_obs[pix] = depth;
             if (AUX) {
                 if (auxm_obs) auxm_obs[pix] = (uint8_t)material;
                 if (auxh_obs) auxh_obs[pix] = h.idx;
-                if (auxf_obs) auxf_obs[pix] = (uint8_t)h.face;
+                if (auxf_obs) auxf_obs[pix] = (uint8_t)face;
             }
         }
         if (PACKED) {
-            // W % 4 == 0: four consecutive lanes hold four consecutive pixels of one row = 12 bytes =
-            // three aligned dwords, written by the first three lanes of the quad: dword m holds the
-            // upper 4-m bytes' worth of pixel m and the lower m+1 bytes of pixel m+1.
+            // four consecutive lanes hold four consecutive pixels of one row = 12 bytes = three aligned
+            // dwords, written by the first three lanes of the quad: dword m holds the upper 4-m bytes'
+            // worth of pixel m and the lower m+1 bytes of pixel m+1.
             const uint32_t next = next_in_quad(colour);
             const uint32_t word = (colour >> (8 * quad)) | (next << (24 - 8 * quad));
-            if (active && quad < 3)
-                *reinterpret_cast<uint32_t*>(rgb_obs + (3u * pix + (uint32_t)quad)) = word;
+            if (quad < 3)
+                *reinterpret_cast<uint32_t*>(rgb_obs + (uint32_t)mad24((int)pix, 3, quad)) = word;
         } else if (active) {
             uint8_t* out = rgb_obs + 3u * pix;
             out[0] = (uint8_t)colour;
@@ -803,7 +808,8 @@ hipError_t prepare_render(size_t lds_bytes)
 hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t stream)
 {
     const bool aux = p.aux_material || p.aux_hit || p.aux_face;
-    const bool packed = (p.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(p.rgb) & 3) == 0);
+    // dword colour stores and unclamped tiles need whole 8x8 tiles and a 4-byte aligned colour tensor
+    const bool packed = (p.W % kTile == 0) && (p.H % kTile == 0) && ((reinterpret_cast<uintptr_t>(p.rgb) & 3) == 0);
     const bool fast = p.g.fast != 0;
     dim3 grid(p.blocks_per_xcd * kXcds), block(p.threads);
 #define MV_LAUNCH(A, P, F) hipLaunchKernelGGL((render_kernel<A, P, F>), grid, block, lds_bytes, stream, p)
