@@ -35,7 +35,7 @@ GridLayout make_layout(int X, int Y, int Z)
 
 static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
-// LDS map (bytes):  [sx: W floats][sy: H floats] | [4 scan-class records, 64 B each] |
+// LDS map (bytes):  [4 scan-class records, 64 B each] | [sx: W floats][sy: H floats] |
 //                   [colour table 7*(M+1) dwords] | bit rows
 // fast grids stage four row arrays (x, x mirrored, y, y mirrored); others stage the x rows only.
 struct LdsMap {
@@ -47,8 +47,8 @@ static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one)
 {
     LdsMap m{};
     size_t off = 0;
-    m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
     m.classes = (uint32_t)off; off += 4 * 64;
+    m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
     m.lut = (uint32_t)off;
     off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
     m.rows = (uint32_t)off;
@@ -369,7 +369,7 @@ struct alignas(16) ScanClass {
     int   face_u;       // face code of a voxel found while scanning along the row
     int   face_v;       // face code of a -v face (add 1 for +v)
     int   mirror_a, mirror_b;   // original u cell = mirror_a + mirror_b * (mirrored cell)
-    int   pad;
+    int   zstride_neg;  // -zstride
 };
 static_assert(sizeof(ScanClass) == 64, "scan class record must be 64 bytes");
 
@@ -469,15 +469,33 @@ __device__ __forceinline__ float vmax(float a, float b)
     return r;
 }
 
+// index of the lowest set bit; the result for 0 is unspecified (callers ignore it for rays that found nothing)
+__device__ __forceinline__ int ctz64_nonzero(uint64_t v)
+{
+    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    uint32_t flo, fhi;
+    asm("v_ffbl_b32 %0, %1" : "=v"(flo) : "v"(lo));
+    asm("v_ffbl_b32 %0, %1" : "=v"(fhi) : "v"(hi));
+    // v_ffbl_b32 returns 0xffffffff for 0, so the unsigned minimum picks the low word whenever it has a bit
+    return (int)min(flo, 32u + fhi);
+}
+
 typedef __attribute__((address_space(3))) const uint64_t* lds_u64_ptr;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_ptr;
 
-// a*b + c on the 24-bit multiplier (full rate); every product on this path fits 24 x 24 bits
+// a*b + c on the 24-bit multiplier (full rate); every product on this path fits 24 x 24 bits.
+// mad24s takes the multiplier b from a scalar register (a wave-uniform value such as a grid dimension).
 __device__ __forceinline__ int mad24(int a, int b, int c)
 {
     int r;
     asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ int mad24s(int a, int b_uniform, int c)
+{
+    int r;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(b_uniform), "v"(c));
     return r;
 }
 
@@ -493,10 +511,12 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
     const float dv = xm ? dy : dx;
-    const int q = (xm ? 0 : 2) + (du < 0.0f ? 1 : 0);
+    // class = 2*(y dominant) + (direction negative); its record sits at 64*class from the start of the
+    // workgroup's dynamic LDS
+    const uint32_t qoff = (xm ? 0u : 128u) | ((__float_as_uint(du) >> 31) << 6);
     ScanClass c;
     {
-        lds_u32x4_ptr rec = (lds_u32x4_ptr)(uintptr_t)(classes_addr + q * 64);
+        lds_u32x4_ptr rec = (lds_u32x4_ptr)(uintptr_t)(classes_addr + qoff);
         u32x4* dst = reinterpret_cast<u32x4*>(&c);
         dst[0] = rec[0]; dst[1] = rec[1]; dst[2] = rec[2]; dst[3] = rec[3];
     }
@@ -515,7 +535,7 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const float t_end = vmin(vmin(c.uexit * inv_u, fmaf(vneg ? c.nv_neg : c.nv_pos, dt_v, t0_v)),
                              fmaf(zneg ? nz_neg : nz_pos, dt_z, t0_z));
     const int sv = vneg ? -8 : 8;
-    const int sz = zneg ? -c.zstride : c.zstride;
+    const int sz = zneg ? c.zstride_neg : c.zstride;
     const float step_v = vneg ? -1.0f : 1.0f, step_z = zneg ? -1.0f : 1.0f;
 
     float t_v = t0_v, t_z = t0_z, n_v = 0.0f, n_z = 0.0f;
@@ -552,7 +572,7 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const bool found = in_range != 0;
 
     // in_range is r moved up so that cell i_last sits at bit 63: its lowest set bit p is cell i_last - (63 - p)
-    const int iu = i_last - 63 + __builtin_ctzll(in_range | (1ull << 63));      // mirrored cell along u
+    const int iu = i_last - 63 + ctz64_nonzero(in_range);                        // mirrored cell along u
     const bool along_row = ((uint32_t)r & 1u) == 0u;                            // not the row's entry cell
     // the row was entered at the later of the last v crossing and the last z crossing (|n|-1; for n = 0
     // the expression is <= 0 because the first plane is at most one cell away)
@@ -569,7 +589,7 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const int k = k0 + (int)n_z;
     const int io = mad24(c.mirror_b, iu, c.mirror_a);
     const int jy = xm ? jv : io, ix = xm ? io : jv;
-    const int idx = mad24(mad24(k, Y, jy), X, ix);
+    const int idx = mad24s(mad24s(k, Y, jy), X, ix);
     Hit h;
     h.idx = found ? idx : -1;       // face and t are only meaningful for idx >= 0; the caller substitutes the miss values
     h.face = face;
@@ -604,9 +624,9 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     const int X = g.X, Y = g.Y, Z = g.Z;
 
     // LDS map, mirrors lds_map() on the host
-    const uint32_t off_scalars = 0;
-    const uint32_t off_classes = (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
-    const uint32_t off_lut = off_classes + 256;
+    const uint32_t off_classes = 0;
+    const uint32_t off_scalars = 256;
+    const uint32_t off_lut = off_scalars + (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
     const uint32_t off_rows = off_lut + (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15);
     float* lds_sx = reinterpret_cast<float*>(lds + off_scalars);
     float* lds_sy = lds_sx + p.W;
@@ -696,7 +716,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         c.face_v = 2 * (xmaj ? 1 : 0);
         c.mirror_a = neg ? U - 1 : 0;
         c.mirror_b = neg ? -1 : 1;
-        c.pad = 0;
+        c.zstride_neg = -8 * V;
         *reinterpret_cast<ScanClass*>(lds + off_classes + q * 64) = c;
     }
     __syncthreads();
@@ -755,13 +775,13 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         int material = 0, face = 255;
         if (hit) {
             material = vox_env[min((uint32_t)h.idx, last_voxel)];
-            colour = lut_lds[mad24(h.face, p.materials_plus_one, min(material, last_material))];
+            colour = lut_lds[mad24s(h.face, p.materials_plus_one, min(material, last_material))];
             depth = h.t;
             face = h.face;
         }
 
         // a7: stores
-        const uint32_t pix = (uint32_t)mad24(crow, p.W, ccol);
+        const uint32_t pix = (uint32_t)mad24s(crow, p.W, ccol);
         if (active) {
             depth_obs[pix] = depth;
             if (AUX) {
@@ -777,7 +797,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
             const uint32_t next = next_in_quad(colour);
             const uint32_t word = (colour >> (8 * quad)) | (next << (24 - 8 * quad));
             if (quad < 3)
-                *reinterpret_cast<uint32_t*>(rgb_obs + (uint32_t)mad24((int)pix, 3, quad)) = word;
+                *reinterpret_cast<uint32_t*>(rgb_obs + (3u * pix + (uint32_t)quad)) = word;
         } else if (active) {
             uint8_t* out = rgb_obs + 3u * pix;
             out[0] = (uint8_t)colour;
