@@ -73,6 +73,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample-envs", type=int, default=4096)
     ap.add_argument("--static-worlds", action="store_true",
                     help="upload the worlds once instead of every step (not the headline number)")
+    ap.add_argument("--sparse-edits", action="store_true",
+                    help="dynamic workload only: send the changed voxels of each step with mv_update_voxels instead "
+                         "of re-uploading whole grids")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy five times, for scaling the HBM byte "
                          "counters of a rocprofv3 --pmc run against a kernel of known traffic")
@@ -123,6 +126,11 @@ def main() -> int:
         grids_d = [torch.from_numpy(g).to(dev) for g in grids]
         cams_d = torch.from_numpy(np.stack(cams_l)).to(dev)
         self_d = torch.from_numpy(np.stack(self_l)).to(dev)
+        edits_d = []
+        if args.sparse_edits:                 # edits that turn grid k-1 into grid k (cyclically)
+            for k in range(n_sets):
+                e, i, m = synth.grid_edits(grids[k - 1], grids[k])
+                edits_d.append(tuple(torch.from_numpy(a).to(dev) for a in (e, i, m)))
     else:
         cams_np = wl.cameras
         if cams_np.shape[0] < 8:
@@ -142,7 +150,9 @@ def main() -> int:
 
     def step(i, ev=None):
         k = i % n_sets
-        if not args.static_worlds or i == 0:
+        if args.sparse_edits and spec.dynamic and i > 0:
+            batch.update_voxels(*edits_d[k], stream=stream)
+        elif not args.static_worlds or i == 0:
             batch.upload_worlds(grids_d[k % len(grids_d)], pal_d, stream=stream)
         batch.set_cameras(cams_d[k], None if self_d is None else self_d[k], stream=stream)
         if ev is not None:
@@ -186,6 +196,8 @@ def main() -> int:
                    "grid": list(spec.grid), "image": [W, H], "num_materials": spec.num_materials,
                    "observations_per_step": n, "camera_sets": int(n_sets),
                    "step": ("render only after one upload" if args.static_worlds else
+                            "mv_update_voxels(device) + mv_set_cameras(device) + mv_render_batch"
+                            if (args.sparse_edits and spec.dynamic) else
                             "mv_upload_worlds(device) + mv_set_cameras(device) + mv_render_batch")},
         "rays_per_s": obs_per_s * rays_per_obs,
         "render_kernel_ms": {"mean": float(render_ms.mean()), "median": float(np.median(render_ms)),

@@ -104,6 +104,22 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out);
 int mv_upload_worlds(mv_batch* batch, int32_t first_env, int32_t count, const uint8_t* voxels,
                      const uint8_t* palette, int32_t src_is_device, void* hip_stream);
 
+/* Change single voxels of worlds that are already uploaded (paper Sec. 3.1-3.2: agents move boxes
+ * and themselves through the voxel grid at every physics step; the state S changes a little per
+ * step, not wholesale).  Edit e sets voxel voxel_index[e] (linear index (k*Y+j)*X+i) of environment
+ * env[e] to material[e]; 0 empties the voxel.
+ *   env, voxel_index : [count] int32;  material : [count] uint8.  All three in host memory if
+ *   src_is_device == 0 (validated: MV_ERR_RANGE for an environment, index or material id out of range,
+ *   nothing is changed), else in device memory (not validated; out-of-range edits are dropped).
+ * One call must not contain two edits of the same voxel (their order would be undefined); send the
+ * clears and the sets of one step as two calls if an object may move into a voxel another one leaves.
+ * The occupancy bit rows are patched in place with atomics; the per-environment "highest solid layer"
+ * bound only grows (it stays a valid bound when the top voxel is removed).  count == 0 is a no-op.
+ * Errors: MV_ERR_ARG, MV_ERR_RANGE, MV_ERR_STATE (an addressed environment has no grid yet; host data
+ * only), MV_ERR_HIP. */
+int mv_update_voxels(mv_batch* batch, int32_t count, const int32_t* env, const int32_t* voxel_index,
+                     const uint8_t* material, int32_t src_is_device, void* hip_stream);
+
 /* Set all N*A cameras (paper Sec. 3.2: cameras are entities of the state S that Render reads).
  *   cams       : [N*A, 5] float32 rows (x, y, z, yaw, pitch), observation order env*A+agent.
  *   self_voxel : [N*A] int32, linear index of the LOWER voxel of the camera's own 1x1x2 body

@@ -120,6 +120,24 @@ int mvo_upload_worlds(mvo_batch* b, int32_t first_env, int32_t count, const uint
     return 0;
 }
 
+int mvo_update_voxels(mvo_batch* b, int32_t count, const int32_t* env, const int32_t* voxel_index,
+                      const uint8_t* material)
+{
+    if (!b || count < 0) return -1;
+    if (count == 0) return 0;
+    if (!env || !voxel_index || !material) return -1;
+    size_t per = voxels_per_env(b);
+    for (int32_t e = 0; e < count; ++e) {
+        if (env[e] < 0 || env[e] >= b->cfg.num_envs) return -3;
+        if (voxel_index[e] < 0 || (size_t)voxel_index[e] >= per) return -3;
+        if (material[e] > b->cfg.num_materials) return -3;
+        if (!b->env_ready[env[e]]) return -2;
+    }
+    for (int32_t e = 0; e < count; ++e)
+        b->vox[(size_t)env[e] * per + (size_t)voxel_index[e]] = material[e];
+    return 0;
+}
+
 int mvo_set_cameras(mvo_batch* b, const float* cams, const int32_t* self_voxel)
 {
     if (!b || !cams) return -1;

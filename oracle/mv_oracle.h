@@ -56,6 +56,9 @@ void mvo_destroy(mvo_batch* b);
 int  mvo_upload_worlds(mvo_batch* b, int32_t first_env, int32_t count,
                        const uint8_t* voxels /* [count,Z,Y,X] */,
                        const uint8_t* palette /* [count,M+1,3] or NULL = keep */);
+/* Sparse edits of uploaded grids: voxel voxel_index[e] of environment env[e] becomes material[e]. */
+int  mvo_update_voxels(mvo_batch* b, int32_t count, const int32_t* env, const int32_t* voxel_index,
+                       const uint8_t* material);
 int  mvo_set_cameras(mvo_batch* b, const float* cams /* [N*A,5] x,y,z,yaw,pitch */,
                      const int32_t* self_voxel /* [N*A] or NULL */);
 

@@ -58,6 +58,7 @@ def _load():
     lib.mvo_destroy.argtypes = [vp]
     lib.mvo_destroy.restype = None
     lib.mvo_upload_worlds.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
+    lib.mvo_update_voxels.argtypes = [vp, C.c_int32, vp, vp, vp]
     lib.mvo_set_cameras.argtypes = [vp, vp, vp]
     lib.mvo_render.argtypes = [vp, C.c_int32, C.c_int32] + [vp] * 8 + [C.c_int32]
     lib.mvo_render_pixels.argtypes = [vp, C.c_int64] + [vp] * 11
@@ -134,6 +135,15 @@ class OracleBatch:
         rc = _load().mvo_upload_worlds(self._h, first_env, voxels.shape[0], _ptr(voxels), _ptr(palette))
         if rc != 0:
             raise ValueError(f"mvo_upload_worlds failed ({rc})")
+
+    def update_voxels(self, env: np.ndarray, voxel_index: np.ndarray, material: np.ndarray):
+        env = np.ascontiguousarray(env, dtype=np.int32)
+        voxel_index = np.ascontiguousarray(voxel_index, dtype=np.int32)
+        material = np.ascontiguousarray(material, dtype=np.uint8)
+        assert env.shape == voxel_index.shape == material.shape and env.ndim == 1
+        rc = _load().mvo_update_voxels(self._h, env.shape[0], _ptr(env), _ptr(voxel_index), _ptr(material))
+        if rc != 0:
+            raise ValueError(f"mvo_update_voxels failed ({rc})")
 
     def set_cameras(self, cams: np.ndarray, self_voxel: Optional[np.ndarray] = None):
         cams = np.ascontiguousarray(cams, dtype=np.float32)

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libmv.so")
 MV_OK, MV_ERR_ARG, MV_ERR_STATE, MV_ERR_RANGE, MV_ERR_CAPACITY, MV_ERR_HIP = 0, -1, -2, -3, -4, -5
 FACE_INSIDE, FACE_MISS = 6, 255
 
-EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_set_cameras",
+EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
            "mv_render_batch", "mv_destroy", "mv_last_error", "mv_debug_occupancy",
            "mv_debug_camera_records")
 
@@ -55,6 +55,7 @@ def load_library():
     lib.mv_default_config.restype = None
     lib.mv_create_batch.argtypes = [C.POINTER(MvConfig), C.POINTER(vp)]
     lib.mv_upload_worlds.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp]
+    lib.mv_update_voxels.argtypes = [vp, C.c_int32, vp, vp, vp, C.c_int32, vp]
     lib.mv_set_cameras.argtypes = [vp, vp, vp, C.c_int32, vp]
     lib.mv_render_batch.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.mv_destroy.argtypes = [vp]
@@ -136,6 +137,16 @@ class Batch:
         if palette is not None and _is_device(palette) != dev:
             raise ValueError("voxels and palette must live in the same memory space")
         _check(load_library().mv_upload_worlds(self._h, first_env, count, _as_ptr(voxels), _as_ptr(palette),
+                                               1 if dev else 0, stream))
+
+    def update_voxels(self, env, voxel_index, material, stream: int = 0) -> None:
+        """Sparse edits: ``env`` i32[count], ``voxel_index`` i32[count], ``material`` u8[count], all three
+        torch CUDA tensors or all three host arrays."""
+        count = int(env.shape[0])
+        dev = _is_device(env)
+        if _is_device(voxel_index) != dev or _is_device(material) != dev:
+            raise ValueError("env, voxel_index and material must live in the same memory space")
+        _check(load_library().mv_update_voxels(self._h, count, _as_ptr(env), _as_ptr(voxel_index), _as_ptr(material),
                                                1 if dev else 0, stream))
 
     def set_cameras(self, cams, self_voxel=None, stream: int = 0) -> None:

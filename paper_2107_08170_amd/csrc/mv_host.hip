@@ -71,6 +71,8 @@ struct mv_batch {
     uint32_t* d_lut = nullptr;
     float* d_sx = nullptr;
     float* d_sy = nullptr;
+    uint8_t* d_edits = nullptr;       // staging for host-supplied voxel edits (grown on demand)
+    size_t edits_capacity = 0;        // in edits
     float* d_cams = nullptr;          // staging for host-supplied cameras
     int32_t* d_self = nullptr;
     mv::CameraRecord* d_rec = nullptr;
@@ -85,7 +87,7 @@ static void free_batch(mv_batch* b)
     if (!b) return;
     (void)hipFree(b->d_vox); (void)hipFree(b->d_bits); (void)hipFree(b->d_ztop); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
     (void)hipFree(b->d_sx); (void)hipFree(b->d_sy); (void)hipFree(b->d_cams); (void)hipFree(b->d_self);
-    (void)hipFree(b->d_rec);
+    (void)hipFree(b->d_rec); (void)hipFree(b->d_edits);
     delete b;
 }
 
@@ -235,6 +237,56 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
         if (!b->env_has_grid[e]) { b->env_has_grid[e] = 1; ++b->envs_with_grid; }
         if (palette && !b->env_has_palette[e]) { b->env_has_palette[e] = 1; ++b->envs_with_palette; }
     }
+    return MV_OK;
+}
+
+int mv_update_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32_t* voxel_index, const uint8_t* material,
+                     int32_t src_is_device, void* hip_stream)
+{
+    if (!b) return fail(MV_ERR_ARG, "mv_update_voxels: null batch");
+    if (count < 0) return fail(MV_ERR_ARG, "mv_update_voxels: negative count");
+    if (count == 0) return MV_OK;
+    if (!env || !voxel_index || !material) return fail(MV_ERR_ARG, "mv_update_voxels: null argument");
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_update_voxels: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int32_t* d_env = env;
+    const int32_t* d_idx = voxel_index;
+    const uint8_t* d_mat = material;
+    if (!src_is_device) {
+        for (int32_t e = 0; e < count; ++e) {
+            if (env[e] < 0 || env[e] >= b->cfg.num_envs)
+                return fail(MV_ERR_RANGE, "mv_update_voxels: edit %d names environment %d", e, env[e]);
+            if (voxel_index[e] < 0 || voxel_index[e] >= b->voxels_per_env)
+                return fail(MV_ERR_RANGE, "mv_update_voxels: edit %d names voxel %d", e, voxel_index[e]);
+            if (material[e] > b->cfg.num_materials)
+                return fail(MV_ERR_RANGE, "mv_update_voxels: edit %d has material id %d > %d", e, (int)material[e],
+                            b->cfg.num_materials);
+            if (!b->env_has_grid[env[e]])
+                return fail(MV_ERR_STATE, "mv_update_voxels: environment %d has no grid yet", env[e]);
+        }
+        if ((size_t)count > b->edits_capacity) {
+            // the staging buffer only ever grows; steady-state steps do not allocate
+            size_t cap = b->edits_capacity ? b->edits_capacity : 4096;
+            while (cap < (size_t)count) cap *= 2;
+            uint8_t* fresh = nullptr;
+            MV_HIP(hipMalloc((void**)&fresh, cap * 9));
+            MV_HIP(hipStreamSynchronize(stream));
+            (void)hipFree(b->d_edits);
+            b->d_edits = fresh;
+            b->edits_capacity = cap;
+        }
+        int32_t* s_env = reinterpret_cast<int32_t*>(b->d_edits);
+        int32_t* s_idx = s_env + b->edits_capacity;
+        uint8_t* s_mat = reinterpret_cast<uint8_t*>(s_idx + b->edits_capacity);
+        MV_HIP(hipMemcpyAsync(s_env, env, (size_t)count * 4, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipMemcpyAsync(s_idx, voxel_index, (size_t)count * 4, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipMemcpyAsync(s_mat, material, (size_t)count, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipStreamSynchronize(stream));
+        d_env = s_env; d_idx = s_idx; d_mat = s_mat;
+    }
+    MV_HIP(mv::launch_update_voxels(d_env, d_idx, d_mat, count, b->d_vox, b->d_bits, b->d_ztop, b->cfg.num_envs,
+                                    b->voxels_per_env, b->cfg.num_materials, b->layout, stream));
     return MV_OK;
 }
 

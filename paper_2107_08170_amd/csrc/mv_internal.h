@@ -71,6 +71,9 @@ LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one);
 hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t stream);
 hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
                        const GridLayout& g, hipStream_t stream);
+hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, const uint8_t* material, int count,
+                                uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
+                                int num_materials, const GridLayout& g, hipStream_t stream);
 hipError_t launch_shade_tables(const uint8_t* palette, uint32_t* lut, int count, int materials_plus_one,
                                const float intensity[kNumFaces], hipStream_t stream);
 hipError_t launch_cameras(const float* cams, const int32_t* self_voxel, CameraRecord* rec, int num_obs,

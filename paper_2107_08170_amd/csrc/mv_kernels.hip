@@ -262,6 +262,47 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
 }
 
 // ------------------------------------------------------------------------------------------
+// update: one thread per edited voxel.  The material byte is overwritten; the voxel's bit in its x row
+// and in its y row is set or cleared with a 64-bit atomic (several edits of one call may share a row
+// word); setting a voxel raises the environment's top-layer bound, clearing never lowers it.
+// ------------------------------------------------------------------------------------------
+__global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int32_t* __restrict__ voxel_index,
+                                     const uint8_t* __restrict__ material, int count, uint8_t* __restrict__ vox,
+                                     uint64_t* __restrict__ bits, int32_t* __restrict__ ztop, int num_envs,
+                                     int voxels_per_env, int num_materials, GridLayout g)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= count) return;
+    const int n = env[e], idx = voxel_index[e];
+    const int m = material[e];
+    if (n < 0 || n >= num_envs || idx < 0 || idx >= voxels_per_env || m > num_materials) return;
+    const int XY = g.X * g.Y;
+    const int k = idx / XY, rem = idx - k * XY, j = rem / g.X, i = rem - j * g.X;
+    vox[(size_t)n * voxels_per_env + idx] = (uint8_t)m;
+    unsigned long long* xrow = reinterpret_cast<unsigned long long*>(bits) + (size_t)n * g.env_words +
+                               ((size_t)k * g.Y + j) * g.rowwords_x + (i >> 6);
+    unsigned long long* yrow = reinterpret_cast<unsigned long long*>(bits) + (size_t)n * g.env_words + g.xrow_words +
+                               ((size_t)k * g.X + i) * g.rowwords_y + (j >> 6);
+    if (m != 0) {
+        atomicOr(xrow, 1ull << (i & 63));
+        atomicOr(yrow, 1ull << (j & 63));
+        atomicMax(ztop + n, k + 1);
+    } else {
+        atomicAnd(xrow, ~(1ull << (i & 63)));
+        atomicAnd(yrow, ~(1ull << (j & 63)));
+    }
+}
+
+hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, const uint8_t* material, int count,
+                                uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
+                                int num_materials, const GridLayout& g, hipStream_t stream)
+{
+    hipLaunchKernelGGL(update_voxels_kernel, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
+                       material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // shade: lut[env][face][m] = round-to-nearest(palette[env][m] * intensity[face]) per channel,
 // two separately rounded float32 operations (multiply, then add 0.5), floor, clamp to 255.
 // ------------------------------------------------------------------------------------------

@@ -272,6 +272,16 @@ def dynamic_step(wl: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     return cur, cams, selfv
 
 
+def grid_edits(before: np.ndarray, after: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """The voxels that differ between two batches of grids, as (env i32[n], voxel_index i32[n],
+    material u8[n]) with the material of ``after``: each changed voxel appears exactly once."""
+    N = before.shape[0]
+    diff = np.nonzero(before.reshape(N, -1) != after.reshape(N, -1))
+    env = diff[0].astype(np.int32)
+    idx = diff[1].astype(np.int32)
+    return env, idx, after.reshape(N, -1)[diff].astype(np.uint8)
+
+
 def generate(index: int, num_envs: Optional[int] = None, steps: Optional[int] = None,
              seed_offset: int = 0) -> Workload:
     """Build workload ``index`` (0-4).  ``num_envs``/``steps`` shrink it for bounded samples;

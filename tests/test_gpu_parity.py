@@ -214,6 +214,88 @@ def test_config3_dynamic_worlds_and_own_bodies(lib, orc):
     assert saw_body == 0        # the own-body rule keeps every camera out of "inside a solid"
 
 
+def test_config3_sparse_edits_match_full_uploads(lib, orc):
+    """Stepping the dynamic workload with mv_update_voxels (only the changed voxels) gives bit for bit
+    the frames of re-uploading whole grids, from device-resident and from host edit lists."""
+    wl = synth.generate(3, num_envs=128)
+    spec = wl.spec
+    mk = lambda: binding.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height)
+    full, sparse_d, sparse_h = mk(), mk(), mk()
+    runs = [GpuRun(b, spec.width, spec.height, aux=True) for b in (full, sparse_d, sparse_h)]
+    ob = orc.OracleBatch(spec.num_envs, spec.agents_per_env, spec.grid, spec.width, spec.height, spec.num_materials)
+    vox, cams, selfv = wl.voxels, wl.cameras[0], wl.self_voxel[0]
+    for b in (full, sparse_d, sparse_h):
+        b.upload_worlds(vox, wl.palette)
+    ob.upload_worlds(vox, wl.palette)
+    total_edits = 0
+    for step in range(5):
+        if step:
+            prev = vox
+            vox, cams, selfv = synth.dynamic_step(wl)
+            env, idx, mat = synth.grid_edits(prev, vox)
+            total_edits += env.size
+            full.upload_worlds(torch.from_numpy(vox).cuda(), None, stream=_stream())
+            sparse_d.update_voxels(torch.from_numpy(env).cuda(), torch.from_numpy(idx).cuda(), torch.from_numpy(mat).cuda(),
+                                   stream=_stream())
+            sparse_h.update_voxels(env, idx, mat, stream=_stream())
+            ob.update_voxels(env, idx, mat)
+            torch.cuda.synchronize()
+        cams_d, self_d = torch.from_numpy(cams).cuda(), torch.from_numpy(selfv).cuda()
+        for b in (full, sparse_d, sparse_h):
+            b.set_cameras(cams_d, self_d, stream=_stream())
+        torch.cuda.synchronize()
+        for r in runs:
+            r.render()
+        for r in runs[1:]:
+            for name in ("rgb", "depth", "material", "hit", "face"):
+                assert torch.equal(getattr(r, name).view(torch.uint8), getattr(runs[0], name).view(torch.uint8)), (step, name)
+        ob.set_cameras(cams, selfv)
+        parity.compare(runs[1].numpy(), ob.render(threads=16), label=f"sparse edits step {step}")
+    assert total_edits > 1000
+
+
+def test_sparse_edits_raise_the_top_layer_and_reject_bad_input(lib, orc):
+    grid = (12, 10, 9)
+    rng = np.random.default_rng(5)
+    vox = np.zeros((2, 9, 10, 12), np.uint8)
+    vox[:, 0] = 1                                           # floor only: highest solid layer is 0
+    pal = rng.integers(0, 256, size=(2, 4, 3), dtype=np.uint8)
+    cams = np.array([[2.5, 5.5, 1.5, 0.0, 0.5], [9.5, 5.5, 1.5, np.pi, 0.4]] * 2, np.float32)
+    spec = _mini_spec(2, 2, grid, 64, 40, 3)
+    run = _gpu_for(spec, vox, pal, cams)
+    ob = _oracle_for(orc, spec, vox, pal, cams)
+    # a floating slab high above the floor, in environment 1 only
+    k, j = 7, np.arange(3, 8)
+    idx = np.array([(k * 10 + jj) * 12 + ii for jj in j for ii in range(4, 9)], np.int32)
+    env = np.ones_like(idx)
+    mat = np.full(idx.shape, 3, np.uint8)
+    run.batch.update_voxels(env, idx, mat)
+    ob.update_voxels(env, idx, mat)
+    run.render()
+    g, ref = run.numpy(), ob.render()
+    parity.compare(g, ref, label="slab added by edits")
+    assert (g.material[2:] == 3).any() and not (g.material[:2] == 3).any()
+    # remove it again: back to the floor-only picture
+    run.batch.update_voxels(env, idx, np.zeros_like(mat))
+    ob.update_voxels(env, idx, np.zeros_like(mat))
+    run.render()
+    parity.compare(run.numpy(), ob.render(), label="slab removed by edits")
+    assert not (run.numpy().material == 3).any()
+    for bad in ((np.array([2], np.int32), np.array([0], np.int32), np.array([1], np.uint8)),
+                (np.array([0], np.int32), np.array([12 * 10 * 9], np.int32), np.array([1], np.uint8)),
+                (np.array([0], np.int32), np.array([5], np.int32), np.array([4], np.uint8))):
+        with pytest.raises(binding.MvError) as e:
+            run.batch.update_voxels(*bad)
+        assert e.value.code == binding.MV_ERR_RANGE
+    run.batch.update_voxels(np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros(0, np.uint8))      # empty: no-op
+    # device-side edits out of range are dropped, not applied
+    run.batch.update_voxels(torch.tensor([5, 0], dtype=torch.int32).cuda(), torch.tensor([0, 10 ** 6], dtype=torch.int32).cuda(),
+                            torch.tensor([1, 1], dtype=torch.uint8).cuda(), stream=_stream())
+    torch.cuda.synchronize()
+    run.render()
+    parity.compare(run.numpy(), ob.render(), label="after dropped edits")
+
+
 # ------------------------------------------------------------------------------------------ config 4
 def test_config4_large_grid_large_image(lib, orc):
     wl = synth.generate(4)

@@ -440,3 +440,42 @@ def test_exact_zero_direction_components(orc):
     out = b.render()
     assert out.hit_index[0, 0, 0] == (2 * 6 + 2) * 6 + 5 and out.depth[0, 0, 0] == 4.5 and out.face[0, 0, 0] == 0
     assert out.hit_index[1, 0, 0] == -1 and out.steps[1, 0, 0] == 6
+
+
+def test_sparse_edits_equal_a_fresh_upload(orc):
+    """mvo_update_voxels is pinned by the plain definition of what an edit is: rendering after the
+    edits equals rendering a batch that received the edited grids wholesale."""
+    rng = np.random.default_rng(77)
+    grid = (9, 7, 5)
+    vox, pal = synth.random_world(rng, 3, grid, 0.2, 6)
+    vox[:, 0] = 2
+    cams = synth.random_cameras(rng, 6, grid, margin=0.0, max_pitch=0.7)
+    after = vox.copy()
+    flip = rng.random(size=vox.shape) < 0.03
+    after[flip] = np.where(vox[flip] == 0, rng.integers(1, 7, size=int(flip.sum()), dtype=np.uint8), 0)
+    env, idx, mat = synth.grid_edits(vox, after)
+    assert env.size == int(flip.sum()) and (mat == after.reshape(3, -1)[env, idx]).all()
+    a = orc.OracleBatch(3, 2, grid, 48, 32, 6)
+    a.upload_worlds(vox, pal)
+    a.update_voxels(env, idx, mat)
+    a.set_cameras(cams)
+    b = orc.OracleBatch(3, 2, grid, 48, 32, 6)
+    b.upload_worlds(after, pal)
+    b.set_cameras(cams)
+    ra, rb = a.render(), b.render()
+    for name in ("rgb", "depth", "material", "hit_index", "face"):
+        np.testing.assert_array_equal(getattr(ra, name), getattr(rb, name))
+    assert not np.array_equal(ra.hit_index, _render_with(orc, grid, vox, pal, cams).hit_index)   # the edits are visible
+    with pytest.raises(ValueError):
+        a.update_voxels(np.array([3], np.int32), np.array([0], np.int32), np.array([1], np.uint8))
+    with pytest.raises(ValueError):
+        a.update_voxels(np.array([0], np.int32), np.array([9 * 7 * 5], np.int32), np.array([1], np.uint8))
+    with pytest.raises(ValueError):
+        a.update_voxels(np.array([0], np.int32), np.array([0], np.int32), np.array([7], np.uint8))
+
+
+def _render_with(orc, grid, vox, pal, cams):
+    b = orc.OracleBatch(vox.shape[0], cams.shape[0] // vox.shape[0], grid, 48, 32, pal.shape[1] - 1)
+    b.upload_worlds(vox, pal)
+    b.set_cameras(cams)
+    return b.render()
