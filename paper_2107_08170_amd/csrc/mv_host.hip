@@ -224,14 +224,13 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
         if (palette) MV_HIP(hipMemcpyAsync(pal_dst, palette, (size_t)count * pal_bytes, hipMemcpyHostToDevice, stream));
         // pageable host memory: make sure the runtime is done reading it before we return
         MV_HIP(hipStreamSynchronize(stream));
-        MV_HIP(mv::launch_pack(vox_dst, vox_dst, bits_dst, ztop_dst, count, b->layout, stream));
+        MV_HIP(mv::launch_pack(vox_dst, vox_dst, bits_dst, ztop_dst, count, b->layout, palette ? pal_dst : nullptr,
+                               pal_dst, lut_dst, b->materials_plus_one, b->intensity, stream));
     } else {
-        if (palette)
-            MV_HIP(hipMemcpyAsync(pal_dst, palette, (size_t)count * pal_bytes, hipMemcpyDeviceToDevice, stream));
-        MV_HIP(mv::launch_pack(voxels, vox_dst, bits_dst, ztop_dst, count, b->layout, stream));
+        // one launch: material copy, bit rows, palette copy and colour tables
+        MV_HIP(mv::launch_pack(voxels, vox_dst, bits_dst, ztop_dst, count, b->layout, palette, pal_dst, lut_dst,
+                               b->materials_plus_one, b->intensity, stream));
     }
-    if (palette)
-        MV_HIP(mv::launch_shade_tables(pal_dst, lut_dst, count, b->materials_plus_one, b->intensity, stream));
 
     for (int e = first_env; e < first_env + count; ++e) {
         if (!b->env_has_grid[e]) { b->env_has_grid[e] = 1; ++b->envs_with_grid; }

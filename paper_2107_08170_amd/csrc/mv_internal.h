@@ -69,13 +69,13 @@ LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one);
 
 // Launchers (mv_kernels.hip).  All enqueue on `stream` and return hipGetLastError().
 hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t stream);
+// pal_src == nullptr keeps the palettes; otherwise [count][M+1][3] device bytes (may equal pal_dst)
 hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
-                       const GridLayout& g, hipStream_t stream);
+                       const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
+                       int materials_plus_one, const float intensity[kNumFaces], hipStream_t stream);
 hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, const uint8_t* material, int count,
                                 uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
                                 int num_materials, const GridLayout& g, hipStream_t stream);
-hipError_t launch_shade_tables(const uint8_t* palette, uint32_t* lut, int count, int materials_plus_one,
-                               const float intensity[kNumFaces], hipStream_t stream);
 hipError_t launch_cameras(const float* cams, const int32_t* self_voxel, CameraRecord* rec, int num_obs,
                           double tan_half_x, double tan_half_y, int plane_voxels, hipStream_t stream);
 hipError_t prepare_render(size_t lds_bytes);

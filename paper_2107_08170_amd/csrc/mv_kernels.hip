@@ -1,8 +1,8 @@
 // HIP kernels (gfx950 / CDNA4) of the batched voxel-world renderer.
 //
 // Hot path (paper Sec. 3.2, Eq. 2: O = Render(S), all N*A views in one GPU request):
-//   pack      : material ids -> occupancy "bit rows" along x and along y (once per world upload)
-//   shade     : palette x face intensity -> per-environment colour table
+//   pack      : material ids -> occupancy "bit rows" along x and along y, and palette x face intensity ->
+//               per-environment colour table (once per world upload)
 //   cameras   : (x,y,z,yaw,pitch) -> 64-byte camera records (float64 trig, float32 result)
 //   render    : a workgroup stages one environment's bit rows in LDS (plus mirrored copies, so that
 //               every ray scans towards increasing bit positions); each wave renders 8x8-pixel
@@ -96,6 +96,22 @@ hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t 
 // ------------------------------------------------------------------------------------------
 constexpr int kPackThreads = 256;
 
+// Colour table entry (a6): round-to-nearest(palette value * face intensity) per channel as two
+// separately rounded float32 operations (multiply, then add 0.5), floor, clamp to 255; r | g<<8 | b<<16.
+struct Intensities { float v[kNumFaces]; };
+
+__device__ __forceinline__ uint32_t shade_entry(const uint8_t* rgb, float intensity)
+{
+    uint32_t packed = 0;
+#pragma unroll
+    for (int ch = 0; ch < 3; ++ch) {
+        float q = floorf(__fadd_rn(__fmul_rn((float)rgb[ch], intensity), 0.5f));
+        q = fminf(fmaxf(q, 0.0f), 255.0f);
+        packed |= (uint32_t)q << (8 * ch);
+    }
+    return packed;
+}
+
 // 1 if the byte is non-zero (one v_min_u32; written as asm because the compiler otherwise expands the
 // idiom into a compare and a select)
 __device__ __forceinline__ uint32_t nonzero(uint32_t byte)
@@ -122,9 +138,23 @@ constexpr int kPackPrefetch = 8;           // dwords of the next layer each lane
 
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
                                                             uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
-                                                            GridLayout g, int vec_ok)
+                                                            GridLayout g, int vec_ok, const uint8_t* __restrict__ pal_src,
+                                                            uint8_t* __restrict__ pal_dst, uint32_t* __restrict__ lut_dst,
+                                                            int materials_plus_one, Intensities I)
 {
     extern __shared__ __align__(16) uint8_t layer_lds[];   // one layer per wave, padded to 16 bytes
+    if (pal_src) {
+        // the environment's palette: private copy, and the colour table lut[face][material]
+        const uint8_t* ps = pal_src + (size_t)blockIdx.x * materials_plus_one * 3;
+        uint8_t* pd = pal_dst + (size_t)blockIdx.x * materials_plus_one * 3;
+        uint32_t* lut = lut_dst + (size_t)blockIdx.x * kNumFaces * materials_plus_one;
+        if (ps != pd)
+            for (int i = threadIdx.x; i < materials_plus_one * 3; i += kPackThreads) pd[i] = ps[i];
+        for (int i = threadIdx.x; i < kNumFaces * materials_plus_one; i += kPackThreads) {
+            const int face = i / materials_plus_one, m = i - face * materials_plus_one;
+            lut[i] = shade_entry(ps + 3 * m, I.v[face]);
+        }
+    }
     __shared__ int top_lds;
     const int env = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -249,15 +279,18 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
 }
 
 hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
-                       const GridLayout& g, hipStream_t stream)
+                       const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
+                       int materials_plus_one, const float intensity[kNumFaces], hipStream_t stream)
 {
+    Intensities I;
+    for (int f = 0; f < kNumFaces; ++f) I.v[f] = intensity[f];
     const size_t XY = (size_t)g.X * g.Y;
     const size_t layer_stride = (XY + 15) & ~(size_t)15;
     const size_t lds = layer_stride * (kPackThreads / 64);
     const int vec_ok = (XY % 4 == 0) && ((reinterpret_cast<uintptr_t>(src) & 3) == 0) &&
                        ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
     hipLaunchKernelGGL(pack_kernel, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst, g,
-                       vec_ok);
+                       vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
     return hipGetLastError();
 }
 
@@ -299,44 +332,6 @@ hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, 
 {
     hipLaunchKernelGGL(update_voxels_kernel, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
                        material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g);
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------
-// shade: lut[env][face][m] = round-to-nearest(palette[env][m] * intensity[face]) per channel,
-// two separately rounded float32 operations (multiply, then add 0.5), floor, clamp to 255.
-// ------------------------------------------------------------------------------------------
-struct Intensities { float v[kNumFaces]; };
-
-__global__ void shade_kernel(const uint8_t* __restrict__ palette, uint32_t* __restrict__ lut, int count,
-                             int materials_plus_one, Intensities I)
-{
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    int per_env = kNumFaces * materials_plus_one;
-    if (i >= count * per_env) return;
-    int env = i / per_env;
-    int r = i - env * per_env;
-    int face = r / materials_plus_one;
-    int m = r - face * materials_plus_one;
-    const uint8_t* pal = palette + ((size_t)env * materials_plus_one + m) * 3;
-    uint32_t packed = 0;
-#pragma unroll
-    for (int ch = 0; ch < 3; ++ch) {
-        float q = floorf(__fadd_rn(__fmul_rn((float)pal[ch], I.v[face]), 0.5f));
-        q = fminf(fmaxf(q, 0.0f), 255.0f);
-        packed |= (uint32_t)q << (8 * ch);
-    }
-    lut[i] = packed;
-}
-
-hipError_t launch_shade_tables(const uint8_t* palette, uint32_t* lut, int count, int materials_plus_one,
-                               const float intensity[kNumFaces], hipStream_t stream)
-{
-    Intensities I;
-    for (int f = 0; f < kNumFaces; ++f) I.v[f] = intensity[f];
-    int total = count * kNumFaces * materials_plus_one;
-    hipLaunchKernelGGL(shade_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, palette, lut, count,
-                       materials_plus_one, I);
     return hipGetLastError();
 }
 
