@@ -142,6 +142,34 @@ int mv_set_cameras(mv_batch* batch, const float* cams, const int32_t* self_voxel
 int mv_render_batch(mv_batch* batch, uint8_t* rgb, float* depth, uint8_t* aux_material,
                     int32_t* aux_hit_index, uint8_t* aux_face, void* hip_stream);
 
+/* Choose which environments the next renders draw (paper App. A.1: environments reset on their own
+ * and the last observation of a finished episode is never synthesised).
+ *   active : [N] uint8, non-zero = render this environment's A observations; NULL = all (default).
+ * Host memory if src_is_device == 0, else device memory; copied on `stream`.  Observations of inactive
+ * environments are not touched by mv_render_batch (whatever the caller's tensors held stays there).
+ * Errors: MV_ERR_ARG, MV_ERR_HIP. */
+int mv_set_active(mv_batch* batch, const uint8_t* active, int32_t src_is_device, void* hip_stream);
+
+/* A horizontal indicator bar drawn over every observation (paper App. A.2: a pixel-space GUI of
+ * geometric primitives, used to show the agents the time left in the episode). */
+typedef struct {
+    int32_t x, y;              /* top-left pixel of the bar                                        */
+    int32_t width, height;     /* in pixels; the bar must lie inside the image                     */
+    uint8_t fill_rgb[3];       /* colour of the filled part (the left fraction of the bar)         */
+    uint8_t empty_rgb[3];      /* colour of the rest of the bar                                    */
+    uint8_t reserved[2];       /* must be 0                                                        */
+} mv_bar;
+
+/* Draw the bar into an already rendered colour tensor, in place, after the render on `stream`.
+ *   rgb      : device [N*A, H, W, 3] uint8 (the tensor given to mv_render_batch).
+ *   fraction : [N*A] float32, the filled share of each observation's bar; host memory if
+ *              src_is_device == 0 (validated: non-finite -> MV_ERR_ARG), else device memory.
+ * The first floor(fraction*width + 0.5) columns of the bar (float32 arithmetic, clamped to
+ * 0..width) take fill_rgb, the others empty_rgb.  Depth is not touched.  Inactive environments
+ * (mv_set_active) are skipped.  Errors: MV_ERR_ARG (null, bar outside the image), MV_ERR_HIP. */
+int mv_draw_bars(mv_batch* batch, uint8_t* rgb, const float* fraction, const mv_bar* bar,
+                 int32_t src_is_device, void* hip_stream);
+
 /* Free the batch and its device memory (synchronises the device first).  NULL is a no-op. */
 void mv_destroy(mv_batch* batch);
 

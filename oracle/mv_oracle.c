@@ -164,6 +164,32 @@ int mvo_set_cameras(mvo_batch* b, const float* cams, const int32_t* self_voxel)
     return 0;
 }
 
+int mvo_draw_bars(const mvo_batch* b, int32_t first_obs, int32_t count, uint8_t* rgb, const float* fraction,
+                  int32_t x, int32_t y, int32_t width, int32_t height, const uint8_t fill_rgb[3],
+                  const uint8_t empty_rgb[3], const uint8_t* active)
+{
+    if (!b || !rgb || !fraction || !fill_rgb || !empty_rgb) return -1;
+    const int32_t W = b->cfg.width, H = b->cfg.height;
+    if (width <= 0 || height <= 0 || x < 0 || y < 0 || x > W - width || y > H - height) return -1;
+    if (first_obs < 0 || count <= 0 || first_obs > b->cfg.num_envs * b->cfg.agents_per_env - count) return -3;
+    for (int32_t o = 0; o < count; ++o) {
+        if (active && !active[(first_obs + o) / b->cfg.agents_per_env]) continue;
+        volatile float prod = fraction[o] * (float)width;
+        volatile float sum = prod + 0.5f;
+        float cols = floorf(sum);
+        if (!(cols > 0.0f)) cols = 0.0f;
+        if (cols > (float)width) cols = (float)width;
+        const int32_t filled = (int32_t)cols;
+        for (int32_t r = 0; r < height; ++r)
+            for (int32_t c = 0; c < width; ++c) {
+                uint8_t* px = rgb + (((size_t)o * H + (size_t)(y + r)) * W + (size_t)(x + c)) * 3;
+                const uint8_t* col = c < filled ? fill_rgb : empty_rgb;
+                px[0] = col[0]; px[1] = col[1]; px[2] = col[2];
+            }
+    }
+    return 0;
+}
+
 int mvo_camera_record(const mvo_batch* b, int32_t obs, float rec[12])
 {
     if (!b || !rec || !b->cams_ready) return -1;

@@ -74,6 +74,15 @@ int  mvo_render_pixels(mvo_batch* b, int64_t n, const int32_t* obs, const int32_
                        int32_t* hit_index, uint8_t* face, int32_t* steps, double* edge_margin,
                        double* t_exact);
 
+/* Indicator bar over rendered colours: for each of the `count` observations starting at first_obs the
+ * first floor(fraction*width + 0.5) columns (float32 arithmetic, clamped to 0..width) of the
+ * width x height rectangle at (x, y) take fill_rgb, the others empty_rgb.  rgb is [count,H,W,3],
+ * fraction [count].  active (may be NULL) is [N]: observations of environments with active == 0 are
+ * left untouched. */
+int  mvo_draw_bars(const mvo_batch* b, int32_t first_obs, int32_t count, uint8_t* rgb, const float* fraction,
+                   int32_t x, int32_t y, int32_t width, int32_t height, const uint8_t fill_rgb[3],
+                   const uint8_t empty_rgb[3], const uint8_t* active);
+
 /* The 12-float camera record (P, F, R, U) of one observation and the float32 ray direction of
  * one pixel, exactly as the renderer uses them. */
 int  mvo_camera_record(const mvo_batch* b, int32_t obs, float rec[12]);

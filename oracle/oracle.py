@@ -62,6 +62,7 @@ def _load():
     lib.mvo_set_cameras.argtypes = [vp, vp, vp]
     lib.mvo_render.argtypes = [vp, C.c_int32, C.c_int32] + [vp] * 8 + [C.c_int32]
     lib.mvo_render_pixels.argtypes = [vp, C.c_int64] + [vp] * 11
+    lib.mvo_draw_bars.argtypes = [vp, C.c_int32, C.c_int32, vp, vp] + [C.c_int32] * 4 + [vp, vp, vp]
     lib.mvo_camera_record.argtypes = [vp, C.c_int32, vp]
     lib.mvo_pixel_ray.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp]
     lib.mvo_face_intensity.argtypes = [vp, vp]
@@ -187,6 +188,22 @@ class OracleBatch:
         if rc != 0:
             raise ValueError(f"mvo_render_pixels failed ({rc})")
         return out
+
+    def draw_bars(self, rgb: np.ndarray, fraction: np.ndarray, x: int, y: int, width: int, height: int,
+                  fill_rgb, empty_rgb, first_obs: int = 0, active: Optional[np.ndarray] = None):
+        """Paint the indicator bar into ``rgb`` (u8[count,H,W,3], modified in place)."""
+        assert rgb.dtype == np.uint8 and rgb.flags.c_contiguous and rgb.shape[1:] == (self.H, self.W, 3)
+        fraction = np.ascontiguousarray(fraction, dtype=np.float32)
+        assert fraction.shape == (rgb.shape[0],)
+        fill = np.asarray(fill_rgb, np.uint8)
+        empty = np.asarray(empty_rgb, np.uint8)
+        if active is not None:
+            active = np.ascontiguousarray(active, dtype=np.uint8)
+            assert active.shape == (self.N,)
+        rc = _load().mvo_draw_bars(self._h, first_obs, rgb.shape[0], _ptr(rgb), _ptr(fraction), x, y, width, height,
+                                   _ptr(fill), _ptr(empty), _ptr(active))
+        if rc != 0:
+            raise ValueError(f"mvo_draw_bars failed ({rc})")
 
     def camera_record(self, obs: int) -> np.ndarray:
         rec = np.empty(12, np.float32)

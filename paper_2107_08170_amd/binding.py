@@ -18,7 +18,7 @@ MV_OK, MV_ERR_ARG, MV_ERR_STATE, MV_ERR_RANGE, MV_ERR_CAPACITY, MV_ERR_HIP = 0, 
 FACE_INSIDE, FACE_MISS = 6, 255
 
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
-           "mv_render_batch", "mv_destroy", "mv_last_error", "mv_debug_occupancy",
+           "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_destroy", "mv_last_error", "mv_debug_occupancy",
            "mv_debug_camera_records")
 
 
@@ -30,6 +30,12 @@ class MvConfig(C.Structure):
                 ("num_materials", C.c_int32), ("light_dir", C.c_float * 3),
                 ("ambient", C.c_float), ("diffuse", C.c_float), ("sky_rgb", C.c_uint8 * 3),
                 ("reserved0", C.c_uint8), ("device", C.c_int32), ("tiles_per_block", C.c_int32)]
+
+
+class MvBar(C.Structure):
+    """Mirror of ``mv_bar``."""
+    _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("width", C.c_int32), ("height", C.c_int32),
+                ("fill_rgb", C.c_uint8 * 3), ("empty_rgb", C.c_uint8 * 3), ("reserved", C.c_uint8 * 2)]
 
 
 class MvError(RuntimeError):
@@ -58,6 +64,8 @@ def load_library():
     lib.mv_update_voxels.argtypes = [vp, C.c_int32, vp, vp, vp, C.c_int32, vp]
     lib.mv_set_cameras.argtypes = [vp, vp, vp, C.c_int32, vp]
     lib.mv_render_batch.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.mv_set_active.argtypes = [vp, vp, C.c_int32, vp]
+    lib.mv_draw_bars.argtypes = [vp, vp, vp, C.POINTER(MvBar), C.c_int32, vp]
     lib.mv_destroy.argtypes = [vp]
     lib.mv_destroy.restype = None
     lib.mv_last_error.restype = C.c_char_p
@@ -158,6 +166,19 @@ class Batch:
     def render(self, rgb, depth, aux_material=None, aux_hit_index=None, aux_face=None, stream: int = 0) -> None:
         _check(load_library().mv_render_batch(self._h, _as_ptr(rgb), _as_ptr(depth), _as_ptr(aux_material),
                                               _as_ptr(aux_hit_index), _as_ptr(aux_face), stream))
+
+    def set_active(self, active, stream: int = 0) -> None:
+        """``active`` u8[N] (non-zero = render) as a torch CUDA tensor or a host array; None = all."""
+        _check(load_library().mv_set_active(self._h, _as_ptr(active), 1 if _is_device(active) else 0, stream))
+
+    def draw_bars(self, rgb, fraction, x: int, y: int, width: int, height: int, fill_rgb, empty_rgb,
+                  stream: int = 0) -> None:
+        bar = MvBar()
+        bar.x, bar.y, bar.width, bar.height = x, y, width, height
+        bar.fill_rgb[:] = [int(v) for v in fill_rgb]
+        bar.empty_rgb[:] = [int(v) for v in empty_rgb]
+        _check(load_library().mv_draw_bars(self._h, _as_ptr(rgb), _as_ptr(fraction), C.byref(bar),
+                                           1 if _is_device(fraction) else 0, stream))
 
     def debug_occupancy(self, env: int):
         """(x_rows_ptr, x_row_words, y_rows_ptr, y_row_words, top_layer_ptr) of one environment."""

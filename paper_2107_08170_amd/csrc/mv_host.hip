@@ -71,6 +71,9 @@ struct mv_batch {
     uint32_t* d_lut = nullptr;
     float* d_sx = nullptr;
     float* d_sy = nullptr;
+    uint8_t* d_active = nullptr;      // [N] render mask
+    bool all_active = true;
+    float* d_fraction = nullptr;      // [N*A] staging for host-supplied bar fractions
     uint8_t* d_edits = nullptr;       // staging for host-supplied voxel edits (grown on demand)
     size_t edits_capacity = 0;        // in edits
     float* d_cams = nullptr;          // staging for host-supplied cameras
@@ -87,7 +90,7 @@ static void free_batch(mv_batch* b)
     if (!b) return;
     (void)hipFree(b->d_vox); (void)hipFree(b->d_bits); (void)hipFree(b->d_ztop); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
     (void)hipFree(b->d_sx); (void)hipFree(b->d_sy); (void)hipFree(b->d_cams); (void)hipFree(b->d_self);
-    (void)hipFree(b->d_rec); (void)hipFree(b->d_edits);
+    (void)hipFree(b->d_rec); (void)hipFree(b->d_edits); (void)hipFree(b->d_active); (void)hipFree(b->d_fraction);
     delete b;
 }
 
@@ -183,6 +186,8 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     alloc((void**)&b->d_cams, (size_t)num_obs * 5 * 4);
     alloc((void**)&b->d_self, (size_t)num_obs * 4);
     alloc((void**)&b->d_rec, (size_t)num_obs * sizeof(mv::CameraRecord));
+    alloc((void**)&b->d_active, N);
+    alloc((void**)&b->d_fraction, (size_t)num_obs * 4);
     if (e == hipSuccess) e = mv::launch_pixel_scalars(b->d_sx, b->d_sy, cfg->width, cfg->height, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
     if (e == hipSuccess) e = mv::prepare_render(plan.bytes);
@@ -331,6 +336,7 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     if (!scope.ok()) return fail(MV_ERR_HIP, "mv_render_batch: cannot select device %d", b->cfg.device);
 
     mv::RenderParams p{};
+    p.active = b->all_active ? nullptr : b->d_active;
     p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
     p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
     p.g = b->layout;
@@ -362,6 +368,49 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.sky_packed = (uint32_t)b->cfg.sky_rgb[0] | ((uint32_t)b->cfg.sky_rgb[1] << 8) | ((uint32_t)b->cfg.sky_rgb[2] << 16);
     p.max_steps = p.g.X + p.g.Y + p.g.Z + 3;
     MV_HIP(mv::launch_render(p, b->plan.bytes, (hipStream_t)hip_stream));
+    return MV_OK;
+}
+
+int mv_set_active(mv_batch* b, const uint8_t* active, int32_t src_is_device, void* hip_stream)
+{
+    if (!b) return fail(MV_ERR_ARG, "mv_set_active: null batch");
+    if (!active) { b->all_active = true; return MV_OK; }
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_set_active: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    MV_HIP(hipMemcpyAsync(b->d_active, active, (size_t)b->cfg.num_envs,
+                          src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, stream));
+    if (!src_is_device) MV_HIP(hipStreamSynchronize(stream));
+    b->all_active = false;
+    return MV_OK;
+}
+
+int mv_draw_bars(mv_batch* b, uint8_t* rgb, const float* fraction, const mv_bar* bar, int32_t src_is_device,
+                 void* hip_stream)
+{
+    if (!b || !rgb || !fraction || !bar) return fail(MV_ERR_ARG, "mv_draw_bars: null argument");
+    if (bar->reserved[0] || bar->reserved[1]) return fail(MV_ERR_ARG, "mv_draw_bars: reserved bytes must be 0");
+    if (bar->width <= 0 || bar->height <= 0 || bar->x < 0 || bar->y < 0 || bar->x > b->cfg.width - bar->width ||
+        bar->y > b->cfg.height - bar->height)
+        return fail(MV_ERR_ARG, "mv_draw_bars: bar %dx%d at (%d,%d) does not fit the %dx%d image", bar->width,
+                    bar->height, bar->x, bar->y, b->cfg.width, b->cfg.height);
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_draw_bars: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const float* d_fraction = fraction;
+    if (!src_is_device) {
+        for (int o = 0; o < b->num_obs; ++o)
+            if (!std::isfinite(fraction[o])) return fail(MV_ERR_ARG, "mv_draw_bars: fraction[%d] is not finite", o);
+        MV_HIP(hipMemcpyAsync(b->d_fraction, fraction, (size_t)b->num_obs * 4, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipStreamSynchronize(stream));
+        d_fraction = b->d_fraction;
+    }
+    mv::BarParams bp{};
+    bp.x = bar->x; bp.y = bar->y; bp.width = bar->width; bp.height = bar->height;
+    bp.fill_packed = (uint32_t)bar->fill_rgb[0] | ((uint32_t)bar->fill_rgb[1] << 8) | ((uint32_t)bar->fill_rgb[2] << 16);
+    bp.empty_packed = (uint32_t)bar->empty_rgb[0] | ((uint32_t)bar->empty_rgb[1] << 8) | ((uint32_t)bar->empty_rgb[2] << 16);
+    MV_HIP(mv::launch_bars(rgb, d_fraction, b->all_active ? nullptr : b->d_active, b->num_obs, b->cfg.agents_per_env,
+                           b->cfg.width, b->cfg.height, bp, stream));
     return MV_OK;
 }
 

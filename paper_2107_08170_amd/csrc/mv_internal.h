@@ -40,6 +40,7 @@ struct RenderParams {
     const uint8_t*      vox;              // [N][V] material ids
     const uint32_t*     lut;              // [N][7][M+1] shaded colours, r | g<<8 | b<<16
     const CameraRecord* rec;              // [N*A]
+    const uint8_t*      active;           // [N] non-zero = render, or nullptr = all
     const float*        sx;               // [W] pixel-centre scalars, (2c+1-W)/W
     const float*        sy;               // [H] (H-2r-1)/H
     uint8_t*            rgb;              // [N*A][H][W][3]
@@ -78,6 +79,12 @@ hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, 
                                 int num_materials, const GridLayout& g, hipStream_t stream);
 hipError_t launch_cameras(const float* cams, const int32_t* self_voxel, CameraRecord* rec, int num_obs,
                           double tan_half_x, double tan_half_y, int plane_voxels, hipStream_t stream);
+struct BarParams {
+    int32_t x, y, width, height;
+    uint32_t fill_packed, empty_packed;   // r | g<<8 | b<<16
+};
+hipError_t launch_bars(uint8_t* rgb, const float* fraction, const uint8_t* active, int num_obs, int A, int W, int H,
+                       const BarParams& bar, hipStream_t stream);
 hipError_t prepare_render(size_t lds_bytes);
 hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t stream);
 

@@ -656,6 +656,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     const int obs = (int)(work / (uint32_t)p.blocks_per_obs);
     const int part = (int)(work - (uint32_t)obs * (uint32_t)p.blocks_per_obs);
     const int env = obs / p.A;
+    if (p.active && p.active[env] == 0) return;         // finished episode: its frame is never drawn
     const GridLayout& g = p.g;
     const int X = g.X, Y = g.Y, Z = g.Z;
 
@@ -841,6 +842,36 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
             out[2] = (uint8_t)(colour >> 16);
         }
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// bars: one workgroup per observation paints the indicator bar over the rendered colours.
+// ------------------------------------------------------------------------------------------
+__global__ void bars_kernel(uint8_t* __restrict__ rgb, const float* __restrict__ fraction,
+                            const uint8_t* __restrict__ active, int A, int W, int H, BarParams bar)
+{
+    const int obs = blockIdx.x;
+    if (active && active[obs / A] == 0) return;
+    // number of filled columns: one float32 multiply, one float32 add, floor, clamp
+    float cols = floorf(__fadd_rn(__fmul_rn(fraction[obs], (float)bar.width), 0.5f));
+    cols = fminf(fmaxf(cols, 0.0f), (float)bar.width);      // NaN falls to 0
+    const int filled = (int)cols;
+    uint8_t* img = rgb + (size_t)obs * H * W * 3;
+    for (int p = threadIdx.x; p < bar.width * bar.height; p += blockDim.x) {
+        const int r = p / bar.width, c = p - r * bar.width;
+        const uint32_t colour = c < filled ? bar.fill_packed : bar.empty_packed;
+        uint8_t* out = img + ((size_t)(bar.y + r) * W + (bar.x + c)) * 3;
+        out[0] = (uint8_t)colour;
+        out[1] = (uint8_t)(colour >> 8);
+        out[2] = (uint8_t)(colour >> 16);
+    }
+}
+
+hipError_t launch_bars(uint8_t* rgb, const float* fraction, const uint8_t* active, int num_obs, int A, int W, int H,
+                       const BarParams& bar, hipStream_t stream)
+{
+    hipLaunchKernelGGL(bars_kernel, dim3(num_obs), dim3(128), 0, stream, rgb, fraction, active, A, W, H, bar);
+    return hipGetLastError();
 }
 
 template <bool AUX, bool PACKED, bool FAST>

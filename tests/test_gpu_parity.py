@@ -434,6 +434,55 @@ def test_largest_grid_the_lds_plan_takes(lib, orc):
     parity.compare(run.numpy(), ob.render(threads=4), label="128x128x32 grid")
 
 
+def test_active_mask_and_indicator_bars(lib, orc):
+    """Inactive environments are neither rendered nor painted (their pixels keep what the caller's
+    tensors held); active ones are bit for bit what a full render gives; bars match the oracle."""
+    wl = synth.generate(1, num_envs=24)
+    spec = wl.spec
+    rng = np.random.default_rng(31)
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
+    ref = ob.render(threads=8)
+    run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0])
+    run.render()
+    full = run.numpy()
+    active = (rng.random(spec.num_envs) < 0.6).astype(np.uint8)
+    active[0], active[1] = 0, 1
+    fractions = rng.uniform(-0.2, 1.2, size=spec.num_obs).astype(np.float32)
+    fractions[:4] = [0.0, 1.0, 0.5, 0.25]
+    bar = dict(x=8, y=4, width=100, height=3, fill_rgb=(255, 255, 0), empty_rgb=(40, 40, 40))
+    want_rgb = ref.rgb.copy()
+    ob.draw_bars(want_rgb, fractions, active=active, **bar)
+    obs_active = np.repeat(active.astype(bool), spec.agents_per_env)
+    for src in ("device", "host"):
+        run.batch.set_active(torch.from_numpy(active).cuda() if src == "device" else active, stream=_stream())
+        run.render()                                          # poisons the outputs first
+        run.batch.draw_bars(run.rgb, torch.from_numpy(fractions).cuda() if src == "device" else fractions,
+                            stream=_stream(), **bar)
+        torch.cuda.synchronize()
+        g = run.numpy()
+        assert (g.rgb[~obs_active] == 7).all() and (g.depth[~obs_active] == -1.0).all() and (g.hit_index[~obs_active] == -7).all()
+        np.testing.assert_array_equal(g.depth[obs_active].view(np.uint32), full.depth[obs_active].view(np.uint32))
+        np.testing.assert_array_equal(g.hit_index[obs_active], full.hit_index[obs_active])
+        # colours: identical to the full render outside the bar, identical to the oracle's bar inside it
+        inside = np.zeros(g.rgb.shape[:3], bool)
+        inside[:, 4:7, 8:108] = True
+        outside = obs_active[:, None, None] & ~inside
+        np.testing.assert_array_equal(g.rgb[outside], full.rgb[outside])
+        np.testing.assert_array_equal(g.rgb[obs_active][:, 4:7, 8:108], want_rgb[obs_active][:, 4:7, 8:108])
+    # back to all environments
+    run.batch.set_active(None)
+    run.render()
+    parity.compare(run.numpy(), ref, label="all active again")
+    with pytest.raises(binding.MvError) as e:
+        run.batch.draw_bars(run.rgb, fractions, 100, 4, 100, 3, (0, 0, 0), (0, 0, 0))
+    assert e.value.code == binding.MV_ERR_ARG
+    bad = fractions.copy()
+    bad[3] = np.inf
+    with pytest.raises(binding.MvError) as e:
+        run.batch.draw_bars(run.rgb, bad, 8, 4, 100, 3, (0, 0, 0), (0, 0, 0))
+    assert e.value.code == binding.MV_ERR_ARG
+
+
 # ------------------------------------------------------------------------------------------ pieces
 def _read_device(ptr, nbytes):
     hip = C.CDLL("libamdhip64.so")

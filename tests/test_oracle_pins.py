@@ -479,3 +479,27 @@ def _render_with(orc, grid, vox, pal, cams):
     b.upload_worlds(vox, pal)
     b.set_cameras(cams)
     return b.render()
+
+
+def test_indicator_bar_closed_form(orc):
+    """The bar's filled width is round-half-up(fraction * width) columns, clamped; nothing outside the
+    rectangle changes; inactive environments are skipped."""
+    b = orc.OracleBatch(3, 2, (4, 4, 4), 64, 40, 2)
+    fractions = np.array([0.0, 1.0, 0.5, 0.26, 0.999, 1.7], np.float32)
+    rgb = np.full((6, 40, 64, 3), 9, np.uint8)
+    x, y, w, h = 5, 3, 20, 4
+    b.draw_bars(rgb, fractions, x, y, w, h, (250, 10, 20), (1, 2, 3), active=np.array([1, 1, 0], np.uint8))
+    for o, f in enumerate(fractions):
+        bar = rgb[o, y:y + h, x:x + w]
+        outside = rgb[o].copy()
+        outside[y:y + h, x:x + w] = 9
+        assert (outside == 9).all()
+        if o >= 4:                                    # environment 2 is inactive
+            assert (bar == 9).all()
+            continue
+        want = min(w, max(0, int(Fraction(float(f)) * w + Fraction(1, 2))))
+        assert (bar[:, :want] == np.array((250, 10, 20), np.uint8)).all()
+        assert (bar[:, want:] == np.array((1, 2, 3), np.uint8)).all()
+        assert {0: 0, 1: 20, 2: 10, 3: 5}[o] == want
+    with pytest.raises(ValueError):
+        b.draw_bars(rgb, fractions, 60, 3, 20, 4, (0, 0, 0), (0, 0, 0))      # sticks out of the image
