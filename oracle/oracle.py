@@ -52,7 +52,31 @@ def _load():
     if _lib is not None:
         return _lib
     build()
-    lib = C.CDLL(_LIB_PATH)
+    _lib = _bind(C.CDLL(_LIB_PATH))
+    return _lib
+
+
+class use_library:
+    """Context manager: run the front end against another build of the oracle sources (the mutation
+    tests compile deliberately broken copies and check that the pins notice)."""
+
+    def __init__(self, path: str):
+        self._path = path
+
+    def __enter__(self):
+        global _lib
+        _load()
+        self._saved = _lib
+        _lib = _bind(C.CDLL(self._path))
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self._saved
+        return False
+
+
+def _bind(lib):
     vp = C.c_void_p
     lib.mvo_create.argtypes = [C.POINTER(_Config), C.POINTER(vp)]
     lib.mvo_destroy.argtypes = [vp]
@@ -70,7 +94,6 @@ def _load():
     lib.mvo_quantise.restype = C.c_uint8
     lib.mvd_first_hit_batch.argtypes = [C.c_int32] * 3 + [vp, C.c_int64] + [vp] * 6
     lib.mvd_first_hit_batch.restype = None
-    _lib = lib
     return lib
 
 

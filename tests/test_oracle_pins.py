@@ -391,6 +391,12 @@ def test_observation_order_and_own_body(orc):
     np.testing.assert_allclose(out.depth[:, centre[0], centre[1]], 4.5, rtol=1e-6)
     # env 1 uses env 1's palette: face +x... agent 0 looks along +x and enters the -x face (unlit)
     assert tuple(out.rgb[2][centre]) == (75, 75, 0) and tuple(out.rgb[0][centre]) == (0, 75, 0)
+    # looking steeply up, the ray leaves through the UPPER voxel of the own body: it must be invisible too
+    up = cams.copy()
+    up[:, 4] = 1.2
+    b.set_cameras(up, selfv)
+    out_up = b.render()
+    assert (out_up.hit_index[:, H // 2, W // 2] == -1).all() and (out_up.face[:, H // 2, W // 2] == 255).all()
     # without the own-body rule every camera would be inside a solid: face 6 everywhere
     b.set_cameras(cams, None)
     out2 = b.render()
@@ -485,7 +491,7 @@ def test_indicator_bar_closed_form(orc):
     """The bar's filled width is round-half-up(fraction * width) columns, clamped; nothing outside the
     rectangle changes; inactive environments are skipped."""
     b = orc.OracleBatch(3, 2, (4, 4, 4), 64, 40, 2)
-    fractions = np.array([0.0, 1.0, 0.5, 0.26, 0.999, 1.7], np.float32)
+    fractions = np.array([0.0, 1.0, 0.5, 0.28, 0.999, 1.7], np.float32)
     rgb = np.full((6, 40, 64, 3), 9, np.uint8)
     x, y, w, h = 5, 3, 20, 4
     b.draw_bars(rgb, fractions, x, y, w, h, (250, 10, 20), (1, 2, 3), active=np.array([1, 1, 0], np.uint8))
@@ -500,6 +506,46 @@ def test_indicator_bar_closed_form(orc):
         want = min(w, max(0, int(Fraction(float(f)) * w + Fraction(1, 2))))
         assert (bar[:, :want] == np.array((250, 10, 20), np.uint8)).all()
         assert (bar[:, want:] == np.array((1, 2, 3), np.uint8)).all()
-        assert {0: 0, 1: 20, 2: 10, 3: 5}[o] == want
+        assert {0: 0, 1: 20, 2: 10, 3: 6}[o] == want          # 0.28 * 20 = 5.6 rounds up to 6
     with pytest.raises(ValueError):
         b.draw_bars(rgb, fractions, 60, 3, 20, 4, (0, 0, 0), (0, 0, 0))      # sticks out of the image
+
+
+def test_pitched_camera_floor_landing_points(orc):
+    """Closed form for a pitched, yawed camera over a solid floor: the pixel ray
+    d = F + sx*R + sy*U with F = (cp*cy, cp*sy, sp), R = tx*(sy_, -cy_, 0), U = ty*(-sp*cy, -sp*sy, cp)
+    reaches the floor plane z = 1 at t = (1 - Pz)/d_z and lands in the cell under P + t*d.  Pins the
+    horizontal components of the up vector and the pitch sign, which the unpitched pins cannot see."""
+    grid = (40, 40, 6)
+    vox = np.zeros((6, 40, 40), np.uint8)
+    vox[0] = 1
+    pal = np.array([[0, 0, 0], [200, 200, 200]], np.uint8)
+    yaw, pitch = 0.9, -0.45
+    cam = np.array([[20.5, 20.5, 2.5, yaw, pitch]], np.float32)
+    _, out = _single(orc, grid, vox, pal, cam)
+    yaw, pitch = float(cam[0, 3]), float(cam[0, 4])
+    cy_, sy_, cp, sp = np.cos(yaw), np.sin(yaw), np.cos(pitch), np.sin(pitch)
+    tx = np.tan(0.5 * HFOV)
+    ty = tx * H / W
+    F = np.array([cp * cy_, cp * sy_, sp])
+    R = tx * np.array([sy_, -cy_, 0.0])
+    U = ty * np.array([-sp * cy_, -sp * sy_, cp])
+    c = np.arange(W)
+    r = np.arange(H)
+    sx = ((2 * c + 1 - W) / W)[None, :, None]
+    sy = ((H - 2 * r - 1) / H)[:, None, None]
+    d = F + sx * R + sy * U                                    # [H,W,3]
+    P = np.array([20.5, 20.5, 2.5])
+    down = d[..., 2] < -1e-9
+    t = np.where(down, (1.0 - P[2]) / np.where(down, d[..., 2], -1.0), 1e9)
+    land = P + t[..., None] * d
+    inside = down & (land[..., 0] > 0) & (land[..., 0] < 40) & (land[..., 1] > 0) & (land[..., 1] < 40)
+    margin = np.abs(land[..., :2] - np.round(land[..., :2])).min(axis=-1)
+    sure = inside & (margin > 1e-4)
+    assert sure.sum() > 4000
+    ij = np.floor(land[..., :2]).astype(int)
+    np.testing.assert_array_equal(out.hit_index[0][sure], (ij[..., 1] * 40 + ij[..., 0])[sure])
+    np.testing.assert_allclose(out.depth[0][sure], t[sure], rtol=2e-6)
+    assert (out.face[0][sure] == 5).all()
+    clear_miss = ~down | (~inside & (np.abs(land[..., :2] - 20).max(axis=-1) > 20.01))
+    assert (out.hit_index[0][clear_miss] == -1).all()
