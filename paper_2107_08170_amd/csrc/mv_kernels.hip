@@ -134,6 +134,45 @@ __device__ __forceinline__ uint64_t gather_row_bits(const uint8_t* cell, int str
     return ((uint64_t)hi << 32) | lo;
 }
 
+// 64x64 bit-matrix transpose across the wave: on entry lane j holds row j, on return lane i holds
+// column i (bit j of the result = bit i of lane j's input).  Recursive block swap: at distance S
+// lanes l and l^S exchange the off-diagonal SxS blocks.  The partner's word comes over the LDS
+// crossbar (ds_swizzle / ds_bpermute, no memory), is rotated so that the wanted block lines up
+// (the bits that wrap around fall on positions the mask discards) and is merged with one bit-select.
+template <int S>
+__device__ __forceinline__ uint32_t swap_blocks(uint32_t w, uint32_t keep, uint32_t rotate_right)
+{
+    const uint32_t partner = (uint32_t)__builtin_amdgcn_ds_swizzle((int)w, (S << 10) | 0x1f);    // lane ^ S
+    const uint32_t lined_up = __builtin_amdgcn_alignbit(partner, partner, rotate_right);
+    return (keep & w) | (~keep & lined_up);
+}
+
+__device__ __forceinline__ uint64_t transpose_bits_across_lanes(uint64_t row, int lane)
+{
+    uint32_t lo = (uint32_t)row, hi = (uint32_t)(row >> 32);
+    {   // distance 32: whole words trade places
+        const bool lower = (lane & 32) == 0;
+        const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)(lower ? hi : lo));
+        const uint32_t nlo = lower ? lo : got, nhi = lower ? got : hi;
+        lo = nlo; hi = nhi;
+    }
+#define MV_SWAP_STAGE(S, MASK)                                                      \
+    {                                                                               \
+        const bool lower = (lane & S) == 0;                                         \
+        const uint32_t keep = lower ? MASK : ~MASK;                                 \
+        const uint32_t rot = lower ? 32 - S : S;                                    \
+        lo = swap_blocks<S>(lo, keep, rot);                                         \
+        hi = swap_blocks<S>(hi, keep, rot);                                         \
+    }
+    MV_SWAP_STAGE(16, 0x0000ffffu)
+    MV_SWAP_STAGE(8, 0x00ff00ffu)
+    MV_SWAP_STAGE(4, 0x0f0f0f0fu)
+    MV_SWAP_STAGE(2, 0x33333333u)
+    MV_SWAP_STAGE(1, 0x55555555u)
+#undef MV_SWAP_STAGE
+    return ((uint64_t)hi << 32) | lo;
+}
+
 constexpr int kPackPrefetch = 8;           // dwords of the next layer each lane keeps in flight
 
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
@@ -236,21 +275,9 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
             const uint64_t xbits = ((uint64_t)hi << 32) | lo;
             seen = xbits;
             if (lane < Y) xrows[(size_t)k * Y + lane] = xbits;
-            // y rows = the transpose of the x-row bit matrix: the x rows go to LDS (over the layer's first
-            // bytes, which every lane has finished reading), then lane i collects bit i of every row j
-            // from broadcast reads.
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            uint64_t* xr = reinterpret_cast<uint64_t*>(mine);
-            if (lane < Y) xr[lane] = xbits;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            uint32_t ylo = 0, yhi = 0;
-#pragma unroll 8
-            for (int j = 0; j < min(Y, 32); ++j) ylo |= ((uint32_t)(xr[j] >> lane) & 1u) << j;
-#pragma unroll 8
-            for (int j = 32; j < Y; ++j) yhi |= ((uint32_t)(xr[j] >> lane) & 1u) << (j - 32);
-            if (lane < X) yrows[(size_t)k * X + lane] = ((uint64_t)yhi << 32) | ylo;
+            // y rows = the transpose of the 64x64 bit matrix whose row j is lane j's x row
+            const uint64_t ybits = transpose_bits_across_lanes(lane < Y ? xbits : 0ull, lane);
+            if (lane < X) yrows[(size_t)k * X + lane] = ybits;
         } else {
         // x rows: row (k*Y + j), word w holds cells i = 64w .. 64w+63
         for (int j0 = 0; j0 < Y; j0 += 64) {
