@@ -217,7 +217,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     if (prefetch && wave < g.Z) {
         const uint32_t* s4 = reinterpret_cast<const uint32_t*>(src + env_vox + (size_t)wave * XY);
 #pragma unroll
-        for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? s4[u * 64 + lane] : 0u;
+        for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? __builtin_nontemporal_load(&s4[u * 64 + lane]) : 0u;
     }
 
     for (int k = wave; k < g.Z; k += waves) {
@@ -231,13 +231,13 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
                 const int b = u * 64 + lane;
                 if (b < n4) {
                     m4[b] = pre[u];
-                    if (copy) d4[b] = pre[u];
+                    if (copy) __builtin_nontemporal_store(pre[u], &d4[b]);
                 }
             }
             if (k + waves < g.Z) {
                 const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc + (size_t)waves * XY);
 #pragma unroll
-                for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? s4[u * 64 + lane] : 0u;
+                for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? __builtin_nontemporal_load(&s4[u * 64 + lane]) : 0u;
             }
         } else if (vec_ok) {
             const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc);
