@@ -182,14 +182,10 @@ const char* mv_last_error(void);
  *                        is voxel (i,j,k); y rows: Z*X rows of *y_row_words words, row k*X+i, bit j
  *                        is voxel (i,j,k); *top_layer points to one int32: 1 + the highest layer k
  *                        that holds a solid voxel (0 for an empty grid).
- *   mv_debug_column_tops : device pointer to uint8 [Y][X]: 1 + the highest layer with a solid voxel in
- *                        each column (0 = empty column) -- an upper bound after mv_update_voxels removed
- *                        voxels; 255 everywhere for grids that do not take the row-scan traversal.
  *   mv_debug_camera_records : device pointer to the [N*A] 64-byte camera records
  *                        (float P[3], F[3], R[3], U[3]; int32 self_lo, self_hi; 8 bytes pad). */
 int mv_debug_occupancy(mv_batch* batch, int32_t env, const uint64_t** x_rows, int32_t* x_row_words,
                        const uint64_t** y_rows, int32_t* y_row_words, const int32_t** top_layer);
-int mv_debug_column_tops(mv_batch* batch, int32_t env, const uint8_t** tops);
 int mv_debug_camera_records(mv_batch* batch, const void** records);
 
 #ifdef __cplusplus

@@ -19,7 +19,7 @@ FACE_INSIDE, FACE_MISS = 6, 255
 
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
            "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_destroy", "mv_last_error", "mv_debug_occupancy",
-           "mv_debug_column_tops", "mv_debug_camera_records")
+           "mv_debug_camera_records")
 
 
 class MvConfig(C.Structure):
@@ -71,7 +71,6 @@ def load_library():
     lib.mv_last_error.restype = C.c_char_p
     lib.mv_debug_occupancy.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_int32), C.POINTER(vp),
                                        C.POINTER(C.c_int32), C.POINTER(vp)]
-    lib.mv_debug_column_tops.argtypes = [vp, C.c_int32, C.POINTER(vp)]
     lib.mv_debug_camera_records.argtypes = [vp, C.POINTER(vp)]
     _lib = lib
     return lib
@@ -188,11 +187,6 @@ class Batch:
         _check(load_library().mv_debug_occupancy(self._h, env, C.byref(xp), C.byref(xw), C.byref(yp), C.byref(yw),
                                                  C.byref(tp)))
         return xp.value, xw.value, yp.value, yw.value, tp.value
-
-    def debug_column_tops(self, env: int) -> int:
-        ptr = C.c_void_p()
-        _check(load_library().mv_debug_column_tops(self._h, env, C.byref(ptr)))
-        return ptr.value
 
     def debug_camera_records(self) -> int:
         ptr = C.c_void_p()

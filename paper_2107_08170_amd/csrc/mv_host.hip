@@ -67,7 +67,6 @@ struct mv_batch {
     uint8_t* d_vox = nullptr;
     uint64_t* d_bits = nullptr;
     int32_t* d_ztop = nullptr;
-    uint8_t* d_coltop = nullptr;      // [N][Y][X] column tops, padded to a multiple of 4 bytes overall
     uint8_t* d_palette = nullptr;
     uint32_t* d_lut = nullptr;
     float* d_sx = nullptr;
@@ -89,7 +88,7 @@ struct mv_batch {
 static void free_batch(mv_batch* b)
 {
     if (!b) return;
-    (void)hipFree(b->d_vox); (void)hipFree(b->d_bits); (void)hipFree(b->d_ztop); (void)hipFree(b->d_coltop); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
+    (void)hipFree(b->d_vox); (void)hipFree(b->d_bits); (void)hipFree(b->d_ztop); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
     (void)hipFree(b->d_sx); (void)hipFree(b->d_sy); (void)hipFree(b->d_cams); (void)hipFree(b->d_self);
     (void)hipFree(b->d_rec); (void)hipFree(b->d_edits); (void)hipFree(b->d_active); (void)hipFree(b->d_fraction);
     delete b;
@@ -180,7 +179,6 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     alloc((void**)&b->d_vox, N * (size_t)voxels);
     alloc((void**)&b->d_bits, N * (size_t)layout.env_words * 8);
     alloc((void**)&b->d_ztop, N * 4);
-    alloc((void**)&b->d_coltop, ((N * (size_t)cfg->grid_x * cfg->grid_y + 3) & ~(size_t)3));
     alloc((void**)&b->d_palette, N * (size_t)b->materials_plus_one * 3);
     alloc((void**)&b->d_lut, N * (size_t)mv::kNumFaces * b->materials_plus_one * 4);
     alloc((void**)&b->d_sx, (size_t)cfg->width * 4);
@@ -218,7 +216,6 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
     uint8_t* pal_dst = b->d_palette + (size_t)first_env * pal_bytes;
     uint64_t* bits_dst = b->d_bits + (size_t)first_env * b->layout.env_words;
     int32_t* ztop_dst = b->d_ztop + first_env;
-    uint8_t* coltop_dst = b->d_coltop + (size_t)first_env * b->cfg.grid_x * b->cfg.grid_y;
     uint32_t* lut_dst = b->d_lut + (size_t)first_env * mv::kNumFaces * b->materials_plus_one;
 
     if (!src_is_device) {
@@ -232,11 +229,11 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
         if (palette) MV_HIP(hipMemcpyAsync(pal_dst, palette, (size_t)count * pal_bytes, hipMemcpyHostToDevice, stream));
         // pageable host memory: make sure the runtime is done reading it before we return
         MV_HIP(hipStreamSynchronize(stream));
-        MV_HIP(mv::launch_pack(vox_dst, vox_dst, bits_dst, ztop_dst, coltop_dst, count, b->layout, palette ? pal_dst : nullptr,
+        MV_HIP(mv::launch_pack(vox_dst, vox_dst, bits_dst, ztop_dst, count, b->layout, palette ? pal_dst : nullptr,
                                pal_dst, lut_dst, b->materials_plus_one, b->intensity, stream));
     } else {
         // one launch: material copy, bit rows, palette copy and colour tables
-        MV_HIP(mv::launch_pack(voxels, vox_dst, bits_dst, ztop_dst, coltop_dst, count, b->layout, palette, pal_dst, lut_dst,
+        MV_HIP(mv::launch_pack(voxels, vox_dst, bits_dst, ztop_dst, count, b->layout, palette, pal_dst, lut_dst,
                                b->materials_plus_one, b->intensity, stream));
     }
 
@@ -292,7 +289,7 @@ int mv_update_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32
         MV_HIP(hipStreamSynchronize(stream));
         d_env = s_env; d_idx = s_idx; d_mat = s_mat;
     }
-    MV_HIP(mv::launch_update_voxels(d_env, d_idx, d_mat, count, b->d_vox, b->d_bits, b->d_ztop, b->d_coltop, b->cfg.num_envs,
+    MV_HIP(mv::launch_update_voxels(d_env, d_idx, d_mat, count, b->d_vox, b->d_bits, b->d_ztop, b->cfg.num_envs,
                                     b->voxels_per_env, b->cfg.num_materials, b->layout, stream));
     return MV_OK;
 }
@@ -340,7 +337,7 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
 
     mv::RenderParams p{};
     p.active = b->all_active ? nullptr : b->d_active;
-    p.bits = b->d_bits; p.ztop = b->d_ztop; p.coltop = b->d_coltop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
+    p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
     p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
     p.g = b->layout;
     p.voxels_per_env = b->voxels_per_env;
@@ -436,14 +433,6 @@ int mv_debug_occupancy(mv_batch* b, int32_t env, const uint64_t** x_rows, int32_
     *y_rows = *x_rows + b->layout.xrow_words;
     *y_row_words = b->layout.rowwords_y;
     *top_layer = b->d_ztop + env;
-    return MV_OK;
-}
-
-int mv_debug_column_tops(mv_batch* b, int32_t env, const uint8_t** tops)
-{
-    if (!b || !tops) return fail(MV_ERR_ARG, "mv_debug_column_tops: null argument");
-    if (env < 0 || env >= b->cfg.num_envs) return fail(MV_ERR_RANGE, "mv_debug_column_tops: env %d", env);
-    *tops = b->d_coltop + (size_t)env * b->cfg.grid_x * b->cfg.grid_y;
     return MV_OK;
 }
 

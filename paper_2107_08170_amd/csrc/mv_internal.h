@@ -31,13 +31,12 @@ struct GridLayout {
     int32_t rowwords_x, rowwords_y;       // 64-bit words per row
     int32_t xrow_words, yrow_words;       // 64-bit words of the x-row / y-row arrays of one environment
     int32_t env_words;                    // xrow_words + yrow_words
-    int32_t fast;                         // 1: X,Y <= 64 (one word per row), Z <= 255 -> row-scan traversal
+    int32_t fast;                         // 1: X,Y <= 64 (one word per row) -> row-scan traversal
 };
 
 struct RenderParams {
     const uint64_t*     bits;             // [N][env_words]
     const int32_t*      ztop;             // [N] 1 + highest solid layer (0 = empty world)
-    const uint8_t*      coltop;           // [N][Y][X] 1 + highest solid layer of each column (fast grids only)
     const uint8_t*      vox;              // [N][V] material ids
     const uint32_t*     lut;              // [N][7][M+1] shaded colours, r | g<<8 | b<<16
     const CameraRecord* rec;              // [N*A]
@@ -72,12 +71,11 @@ LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one);
 // Launchers (mv_kernels.hip).  All enqueue on `stream` and return hipGetLastError().
 hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t stream);
 // pal_src == nullptr keeps the palettes; otherwise [count][M+1][3] device bytes (may equal pal_dst)
-hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, uint8_t* coltop_dst,
-                       int count,
+hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
                        const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
                        int materials_plus_one, const float intensity[kNumFaces], hipStream_t stream);
 hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, const uint8_t* material, int count,
-                                uint8_t* vox, uint64_t* bits, int32_t* ztop, uint8_t* coltop, int num_envs, int voxels_per_env,
+                                uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
                                 int num_materials, const GridLayout& g, hipStream_t stream);
 hipError_t launch_cameras(const float* cams, const int32_t* self_voxel, CameraRecord* rec, int num_obs,
                           double tan_half_x, double tan_half_y, int plane_voxels, hipStream_t stream);

@@ -29,7 +29,7 @@ GridLayout make_layout(int X, int Y, int Z)
     g.xrow_words = Z * Y * g.rowwords_x;
     g.yrow_words = Z * X * g.rowwords_y;
     g.env_words = g.xrow_words + g.yrow_words;
-    g.fast = (X <= 64 && Y <= 64 && Z <= 255) ? 1 : 0;
+    g.fast = (X <= 64 && Y <= 64) ? 1 : 0;
     return g;
 }
 
@@ -177,7 +177,6 @@ constexpr int kPackPrefetch = 8;           // dwords of the next layer each lane
 
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
                                                             uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
-                                                            uint8_t* __restrict__ coltop_dst, int rows_in_lds,
                                                             GridLayout g, int vec_ok, const uint8_t* __restrict__ pal_src,
                                                             uint8_t* __restrict__ pal_dst, uint32_t* __restrict__ lut_dst,
                                                             int materials_plus_one, Intensities I)
@@ -203,8 +202,6 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     const int XY = X * Y;
     const int layer_stride = (XY + 15) & ~15;
     uint8_t* mine = layer_lds + (size_t)wave * layer_stride;
-    // behind the per-wave layers: the environment's x rows, kept for the column tops (fast grids, if they fit)
-    uint64_t* xrows_lds = reinterpret_cast<uint64_t*>(layer_lds + (size_t)waves * layer_stride);
     const size_t env_vox = (size_t)env * XY * g.Z;
     const bool copy = (src != vox_dst);
     uint64_t* xrows = bits_dst + (size_t)env * g.env_words;
@@ -277,10 +274,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
             }
             const uint64_t xbits = ((uint64_t)hi << 32) | lo;
             seen = xbits;
-            if (lane < Y) {
-                xrows[(size_t)k * Y + lane] = xbits;
-                if (rows_in_lds) xrows_lds[k * Y + lane] = xbits;
-            }
+            if (lane < Y) xrows[(size_t)k * Y + lane] = xbits;
             // y rows = the transpose of the 64x64 bit matrix whose row j is lane j's x row
             const uint64_t ybits = transpose_bits_across_lanes(lane < Y ? xbits : 0ull, lane);
             if (lane < X) yrows[(size_t)k * X + lane] = ybits;
@@ -309,41 +303,21 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     if (lane == 0) atomicMax(&top_lds, top);
     __syncthreads();
     if (threadIdx.x == 0) ztop_dst[env] = top_lds;
-    // column tops: 1 + the highest solid layer of every (i,j) column; 255 ("cannot look over it") when the
-    // rows were not kept
-    if (coltop_dst) {
-        uint8_t* tops = coltop_dst + (size_t)env * XY;
-        for (int c = threadIdx.x; c < XY; c += kPackThreads) {
-            int t = 255;
-            if (rows_in_lds) {
-                const int j = c / X, i = c - j * X;
-                t = 0;
-                for (int k = top_lds - 1; k >= 0; --k)
-                    if ((xrows_lds[k * Y + j] >> i) & 1ull) { t = k + 1; break; }
-            }
-            tops[c] = (uint8_t)t;
-        }
-    }
 }
 
-static bool X_is_multiple_of_4(const GridLayout& g) { return (g.X & 3) == 0; }   // the "quick" row path of pack_kernel
-
-hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, uint8_t* coltop_dst,
-                       int count, const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
+hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
+                       const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
                        int materials_plus_one, const float intensity[kNumFaces], hipStream_t stream)
 {
     Intensities I;
     for (int f = 0; f < kNumFaces; ++f) I.v[f] = intensity[f];
     const size_t XY = (size_t)g.X * g.Y;
     const size_t layer_stride = (XY + 15) & ~(size_t)15;
-    size_t lds = layer_stride * (kPackThreads / 64);
-    const size_t rows_bytes = (size_t)g.xrow_words * 8;
-    const int rows_in_lds = g.fast && (X_is_multiple_of_4(g)) && lds + rows_bytes <= 48 * 1024;
-    if (rows_in_lds) lds += rows_bytes;
+    const size_t lds = layer_stride * (kPackThreads / 64);
     const int vec_ok = (XY % 4 == 0) && ((reinterpret_cast<uintptr_t>(src) & 3) == 0) &&
                        ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
-    hipLaunchKernelGGL(pack_kernel, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
-                       coltop_dst, rows_in_lds, g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
+    hipLaunchKernelGGL(pack_kernel, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst, g,
+                       vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
     return hipGetLastError();
 }
 
@@ -354,9 +328,8 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
 // ------------------------------------------------------------------------------------------
 __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int32_t* __restrict__ voxel_index,
                                      const uint8_t* __restrict__ material, int count, uint8_t* __restrict__ vox,
-                                     uint64_t* __restrict__ bits, int32_t* __restrict__ ztop,
-                                     uint8_t* __restrict__ coltop, int num_envs, int voxels_per_env,
-                                     int num_materials, GridLayout g)
+                                     uint64_t* __restrict__ bits, int32_t* __restrict__ ztop, int num_envs,
+                                     int voxels_per_env, int num_materials, GridLayout g)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= count) return;
@@ -374,20 +347,6 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
         atomicOr(xrow, 1ull << (i & 63));
         atomicOr(yrow, 1ull << (j & 63));
         atomicMax(ztop + n, k + 1);
-        if (coltop && g.fast) {
-            // byte-wide maximum through a compare-and-swap on the containing dword; like ztop the column top
-            // only grows, so it stays a valid upper bound when voxels are removed
-            const size_t byte = (size_t)n * XY + rem;
-            unsigned int* word = reinterpret_cast<unsigned int*>(coltop) + (byte >> 2);
-            const unsigned int shift = (unsigned int)(byte & 3) * 8;
-            unsigned int seen = *word;
-            while (((seen >> shift) & 0xffu) < (unsigned int)(k + 1)) {
-                const unsigned int want = (seen & ~(0xffu << shift)) | ((unsigned int)(k + 1) << shift);
-                const unsigned int prev = atomicCAS(word, seen, want);
-                if (prev == seen) break;
-                seen = prev;
-            }
-        }
     } else {
         atomicAnd(xrow, ~(1ull << (i & 63)));
         atomicAnd(yrow, ~(1ull << (j & 63)));
@@ -395,11 +354,11 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
 }
 
 hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, const uint8_t* material, int count,
-                                uint8_t* vox, uint64_t* bits, int32_t* ztop, uint8_t* coltop, int num_envs, int voxels_per_env,
+                                uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
                                 int num_materials, const GridLayout& g, hipStream_t stream)
 {
     hipLaunchKernelGGL(update_voxels_kernel, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
-                       material, count, vox, bits, ztop, coltop, num_envs, voxels_per_env, num_materials, g);
+                       material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g);
     return hipGetLastError();
 }
 

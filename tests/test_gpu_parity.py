@@ -576,13 +576,6 @@ def test_pack_kernel_bit_exact(lib, grid):
         layers = np.nonzero(occ.any(axis=(1, 2)))[0]
         top = int(_read_device(tp, 4).view(np.int32)[0])
         assert top == (int(layers.max()) + 1 if layers.size else 0)
-        # column tops: 1 + highest solid layer per (j,i) column where the row-scan path keeps them, else 255
-        tops = _read_device(batch.debug_column_tops(env), X * Y).reshape(Y, X)
-        if X <= 64 and Y <= 64 and X % 4 == 0:
-            want_tops = np.where(occ, np.arange(1, Z + 1)[:, None, None], 0).max(axis=0)
-            np.testing.assert_array_equal(tops, want_tops)
-        else:
-            assert (tops == 255).all()
 
 
 def test_camera_records_match_the_oracle(lib, orc):
