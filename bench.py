@@ -62,6 +62,32 @@ def measured_traffic(workload: str):
     return None
 
 
+def input_digest(wl) -> str:
+    """SHA-256 over the generated grids, palettes and cameras: identifies the synthetic input of a run."""
+    import hashlib
+    import numpy as np
+    h = hashlib.sha256()
+    for a in (wl.voxels, wl.palette, wl.cameras):
+        h.update(np.ascontiguousarray(a).data)
+    return h.hexdigest()
+
+
+def device_copy_rate(torch) -> float:
+    """Read + written GB/s of a plain 512 MiB device-to-device copy: what HBM delivers to a streaming
+    kernel on this GPU, quoted next to the 8 TB/s datasheet peak."""
+    nbytes = 512 << 20
+    src = torch.full((nbytes,), 5, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    return 2.0 * nbytes * 5 / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,6 +230,7 @@ def main() -> int:
                              "p95": float(np.percentile(render_ms, 95))},
         "render_only_obs_per_s": n / (render_ms.mean() * 1e-3),
         "generator_seconds": gen_s,
+        "input_sha256": input_digest(wl),
     }
     traffic = measured_traffic(spec.name)
     mean_steps = ORACLE_MEAN_STEPS.get(args.config)
@@ -217,7 +244,8 @@ def main() -> int:
                               "algorithmic_ops_per_launch": alg_ops, "oracle_mean_steps_per_ray": mean_steps}
     result["hbm_roofline"] = {"bound": "hbm", "kernel": "mv::render_kernel", "achieved": achieved,
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                              "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes}
+                              "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
+                              "device_copy_GBs": device_copy_rate(torch)}
 
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
@@ -236,11 +264,15 @@ def main() -> int:
             passes += 1
             cpu_s = time.perf_counter() - t0
         steps_sample = ob.render(first_obs=0, count=min(64, envs * spec.agents_per_env), threads=cores).steps
+        t1 = time.perf_counter()
+        ob.render(first_obs=0, count=min(64, envs * spec.agents_per_env), threads=1, side_channels=False)
+        one_core = min(64, envs * spec.agents_per_env) / (time.perf_counter() - t1)
         result["cpu_baseline"] = {"value": passes * envs * spec.agents_per_env / cpu_s, "unit": "observations/s",
                                   "cores": cores, "kind": "oracle",
                                   "sample": f"{passes} passes over the first {envs} environments "
                                             f"({envs * spec.agents_per_env} observations) of camera set 0, "
                                             f"{cpu_s:.2f} s wall on {cores} threads",
+                                  "one_core_value": one_core,
                                   "mean_dda_steps_per_ray": float(steps_sample.mean())}
     print(json.dumps(result))
     return 0
