@@ -428,10 +428,11 @@ struct alignas(16) ScanClass {
     int   i0;           // camera cell along u (mirrored)
     int   zstride;      // bytes between rows of consecutive layers: 8 * V
     int   um1;          // U - 1
-    int   j0;           // camera cell along v
+    int   idx0;         // voxel index of (mirrored cell 0, camera's v cell, camera's layer)
     int   face_u;       // face code of a voxel found while scanning along the row
     int   face_v;       // face code of a -v face (add 1 for +v)
-    int   mirror_a, mirror_b;   // original u cell = mirror_a + mirror_b * (mirrored cell)
+    int   stride_u;     // voxel-index step per mirrored u cell: +-1 (x scans) or +-X (y scans)
+    int   stride_v;     // voxel-index step per v cell: X (x scans) or 1 (y scans)
     int   zstride_neg;  // -zstride
 };
 static_assert(sizeof(ScanClass) == 64, "scan class record must be 64 bytes");
@@ -517,6 +518,10 @@ __device__ __forceinline__ Hit trace_generic(const uint32_t* __restrict__ xrows3
     return miss;
 }
 
+// three-operand forms of the same
+__device__ __forceinline__ float vmax3(float a, float b, float c);
+__device__ __forceinline__ float vmin3(float a, float b, float c);
+
 // One-instruction min/max: fminf()/fmaxf() make the compiler quiet possible signalling NaNs first
 // (an extra v_max per operand inside the loop); no operand here can be one.
 __device__ __forceinline__ float vmin(float a, float b)
@@ -529,6 +534,18 @@ __device__ __forceinline__ float vmax(float a, float b)
 {
     float r;
     asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float vmin3(float a, float b, float c)
+{
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
 
@@ -567,9 +584,9 @@ __device__ __forceinline__ int mad24s(int a, int b_uniform, int c)
 // every input: each turn advances n_v or n_z, the crossing parameters |n|*dt + t0 never decrease, and
 // t_end is that same expression at the last plane of each axis, so t_out reaches t_end after at most
 // V + Z + 2 turns; a NaN anywhere makes the comparison false and ends it at once.
-// n_v and n_z count crossings with the sign of the direction, so that the cell is j0 + n_v, k0 + n_z.
+// n_v and n_z count crossings with the sign of the direction, so that the cell is (v0 + n_v, k0 + n_z).
 __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz, float hi_z, float lo_z,
-                                          float nz_pos, float nz_neg, int k0, int X, int Y)
+                                          float nz_pos, float nz_neg, int XY)
 {
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
@@ -595,8 +612,8 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const float t0_v = vmax(c.hi_v * inv_v, c.lo_v * inv_v);
     const float t0_z = vmax(hi_z * inv_z, lo_z * inv_z);
     // leaving the grid: same |n|*dt + t0 expression as the crossings, so the comparison below is exact
-    const float t_end = vmin(vmin(c.uexit * inv_u, fmaf(vneg ? c.nv_neg : c.nv_pos, dt_v, t0_v)),
-                             fmaf(zneg ? nz_neg : nz_pos, dt_z, t0_z));
+    const float t_end = vmin3(c.uexit * inv_u, fmaf(vneg ? c.nv_neg : c.nv_pos, dt_v, t0_v),
+                              fmaf(zneg ? nz_neg : nz_pos, dt_z, t0_z));
     const int sv = vneg ? -8 : 8;
     const int sz = zneg ? c.zstride_neg : c.zstride;
     const float step_v = vneg ? -1.0f : 1.0f, step_z = zneg ? -1.0f : 1.0f;
@@ -642,17 +659,18 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const float tv_last = fmaf(fabsf(n_v) - 1.0f, dt_v, t0_v);
     const float tz_last = fmaf(fabsf(n_z) - 1.0f, dt_z, t0_z);
     const bool via_z = tz_last >= tv_last;
-    const float t_in = vmax(vmax(tv_last, tz_last), 0.0f);
-    const bool started_here = (__float_as_uint(n_v) | __float_as_uint(n_z)) == 0u;
+    // A hit in the row's entry cell was entered through the later of the two crossings.  The camera's own
+    // cell is never solid here (the caller handles that camera before tracing), so the only way to find
+    // the entry cell of the first row solid is a camera exactly on a cell boundary looking into the
+    // neighbour: both crossings are <= 0 then and the hit is at t = 0 on that boundary.
+    const float t_in = vmax3(tv_last, tz_last, 0.0f);
     const float t_u = ((float)iu - c.Pu) * inv_u;
     const int face_vz = via_z ? (zneg ? 5 : 4) : c.face_v + (vneg ? 1 : 0);
-    const int face = along_row ? c.face_u : (started_here ? 6 : face_vz);
+    const int face = along_row ? c.face_u : face_vz;
     const float t = along_row ? t_u : t_in;
-    const int jv = c.j0 + (int)n_v;
-    const int k = k0 + (int)n_z;
-    const int io = mad24(c.mirror_b, iu, c.mirror_a);
-    const int jy = xm ? jv : io, ix = xm ? io : jv;
-    const int idx = mad24s(mad24s(k, Y, jy), X, ix);
+    // voxel index: the class record holds the index of (mirrored cell 0, camera's v cell, camera's layer)
+    // and the index steps per cell along u (mirroring folded into the sign) and v
+    const int idx = mad24s((int)n_z, XY, mad24((int)n_v, c.stride_v, mad24(iu, c.stride_u, c.idx0)));
     Hit h;
     h.idx = found ? idx : -1;       // face and t are only meaningful for idx >= 0; the caller substitutes the miss values
     h.face = face;
@@ -766,20 +784,22 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         c.Pu = neg ? (float)U - pu : pu;
         c.uexit = (float)U - c.Pu;
         c.i0 = min(max((int)floorf(c.Pu), 0), U - 1);
-        c.j0 = min(max((int)floorf(pv), 0), V - 1);
-        c.hi_v = (float)(c.j0 + 1) - pv;
-        c.lo_v = (float)c.j0 - pv;
-        c.nv_pos = (float)(V - 1 - c.j0);
-        c.nv_neg = (float)c.j0;
+        const int j0 = min(max((int)floorf(pv), 0), V - 1);
+        c.hi_v = (float)(j0 + 1) - pv;
+        c.lo_v = (float)j0 - pv;
+        c.nv_pos = (float)(V - 1 - j0);
+        c.nv_neg = (float)j0;
         const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? g.xrow_words : 0)
                                                                    : 2 * g.xrow_words + (neg ? g.yrow_words : 0));
-        c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(k0 * V + c.j0));
+        c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(k0 * V + j0));
         c.zstride = 8 * V;
         c.um1 = U - 1;
         c.face_u = 2 * (xmaj ? 0 : 1) + (neg ? 1 : 0);
         c.face_v = 2 * (xmaj ? 1 : 0);
-        c.mirror_a = neg ? U - 1 : 0;
-        c.mirror_b = neg ? -1 : 1;
+        const int su = xmaj ? 1 : X;                       // voxel-index step per original u cell
+        c.stride_u = neg ? -su : su;
+        c.stride_v = xmaj ? X : 1;
+        c.idx0 = k0 * X * Y + j0 * c.stride_v + (neg ? (U - 1) * su : 0);
         c.zstride_neg = -8 * V;
         *reinterpret_cast<ScanClass*>(lds + off_classes + q * 64) = c;
     }
@@ -791,6 +811,15 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     const int zlim = ztop > k0 ? ztop : Z;
     const float hi_z = (float)(k0 + 1) - P[2], lo_z = (float)k0 - P[2];
     const float nz_pos = (float)(zlim - 1 - k0), nz_neg = (float)k0;
+
+    // A camera inside a solid voxel (its own body is already gone) sees that voxel everywhere, at depth 0
+    // with the "inside" face: one test per workgroup instead of one per ray.
+    int cam_idx = -1;
+    if (FAST && origin_in_grid) {
+        const int ic = min(max((int)floorf(P[0]), 0), X - 1), jc = min(max((int)floorf(P[1]), 0), Y - 1);
+        const uint32_t bit = (uint32_t)(lds_rows[k0 * Y + jc] >> ic) & 1u;
+        if (__builtin_amdgcn_readfirstlane((int)bit)) cam_idx = (k0 * Y + jc) * X + ic;
+    }
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int waves = threads >> 6;
@@ -826,9 +855,13 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
 
         // a5: traversal
         Hit h;
-        if (FAST && origin_in_grid)
-            h = trace_rows(lds_base + off_classes, d[0], d[1], d[2], hi_z, lo_z, nz_pos, nz_neg, k0, X, Y);
-        else
+        if (FAST && origin_in_grid) {
+            if (cam_idx >= 0) {
+                h.idx = cam_idx; h.face = 6; h.t = 0.0f;
+            } else {
+                h = trace_rows(lds_base + off_classes, d[0], d[1], d[2], hi_z, lo_z, nz_pos, nz_neg, X * Y);
+            }
+        } else
             h = trace_generic(reinterpret_cast<const uint32_t*>(lds_rows), 2 * g.rowwords_x, P, d, X, Y, Z,
                               origin_in_grid, p.max_steps);
 
