@@ -30,10 +30,11 @@ ORACLE_MEAN_STEPS = {1: 8.75, 2: 8.98, 3: 8.45, 4: 10.20}
 
 
 def algorithmic_lane_ops_per_ray(mean_steps: float) -> float:
-    """ALU work a plain per-cell DDA ray caster needs per ray: 13 lane-instructions per step (select the
-    nearest plane, advance, recompute its crossing, test one bit) plus 80 fixed (ray set-up with three
-    reciprocals, hit point, shading, stores)."""
-    return 13.0 * mean_steps + 80.0
+    """ALU work a plain per-cell DDA ray caster cannot do without, per ray: 10 lane-instructions per step
+    (select the nearest plane, advance the cell, recompute that crossing, address and test one bit) plus
+    60 fixed (ray set-up with three reciprocals, hit point and face, shading look-up, stores): the low
+    ends of the ranges a hand count gives (10-15 and 60-100)."""
+    return 10.0 * mean_steps + 60.0
 
 
 def algorithmic_bytes_per_obs(spec) -> float:

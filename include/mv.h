@@ -32,6 +32,7 @@
 #ifndef MV_H
 #define MV_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -169,6 +170,24 @@ typedef struct {
  * (mv_set_active) are skipped.  Errors: MV_ERR_ARG (null, bar outside the image), MV_ERR_HIP. */
 int mv_draw_bars(mv_batch* batch, uint8_t* rgb, const float* fraction, const mv_bar* bar,
                  int32_t src_is_device, void* hip_stream);
+
+/* Pinned (page-locked) host memory for CPU consumers of the observations (paper Sec. 3.2: the images can
+ * stay on the GPU for a GPU learner; a CPU learner or a logger reads them back).  Copies into memory
+ * from mv_host_alloc run asynchronously at full PCIe rate; plain malloc'd memory also works with
+ * mv_fetch_observations but makes that call wait for the copy.  mv_host_free(NULL) is a no-op; free
+ * only after every copy into the block has completed.  Errors: MV_ERR_ARG, MV_ERR_HIP. */
+int mv_host_alloc(void** out, size_t bytes);
+void mv_host_free(void* ptr);
+
+/* Copy observations first_obs .. first_obs+count-1 from the rendered device tensors to host memory on
+ * `stream`, after the render on the same stream:
+ *   rgb_dev, depth_dev   : the tensors given to mv_render_batch (device [N*A,H,W,3] uint8, [N*A,H,W] float32).
+ *   rgb_host, depth_host : destination of count*H*W*3 bytes / count*H*W floats; either may be NULL to skip it
+ *                          (then its device tensor may be NULL too).
+ * Returns without synchronising: the host data is complete once the stream has passed this call
+ * (hipStreamSynchronize or an event).  Errors: MV_ERR_ARG, MV_ERR_RANGE (observation range), MV_ERR_HIP. */
+int mv_fetch_observations(mv_batch* batch, const uint8_t* rgb_dev, const float* depth_dev, int32_t first_obs,
+                          int32_t count, uint8_t* rgb_host, float* depth_host, void* hip_stream);
 
 /* Free the batch and its device memory (synchronises the device first).  NULL is a no-op. */
 void mv_destroy(mv_batch* batch);

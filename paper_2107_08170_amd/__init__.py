@@ -5,4 +5,4 @@ agent camera of thousands of voxel environments per step) behind a five-call C A
 seeded synthetic workloads; ``build`` compiles the library in-tree.
 """
 from . import binding, synth  # noqa: F401
-from .binding import Batch, MvError, load_library  # noqa: F401
+from .binding import Batch, MvError, PinnedBuffer, load_library  # noqa: F401

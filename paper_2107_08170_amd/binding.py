@@ -18,8 +18,8 @@ MV_OK, MV_ERR_ARG, MV_ERR_STATE, MV_ERR_RANGE, MV_ERR_CAPACITY, MV_ERR_HIP = 0, 
 FACE_INSIDE, FACE_MISS = 6, 255
 
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
-           "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_destroy", "mv_last_error", "mv_debug_occupancy",
-           "mv_debug_camera_records")
+           "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_host_alloc", "mv_host_free",
+           "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records")
 
 
 class MvConfig(C.Structure):
@@ -66,6 +66,10 @@ def load_library():
     lib.mv_render_batch.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.mv_set_active.argtypes = [vp, vp, C.c_int32, vp]
     lib.mv_draw_bars.argtypes = [vp, vp, vp, C.POINTER(MvBar), C.c_int32, vp]
+    lib.mv_host_alloc.argtypes = [C.POINTER(vp), C.c_size_t]
+    lib.mv_host_free.argtypes = [vp]
+    lib.mv_host_free.restype = None
+    lib.mv_fetch_observations.argtypes = [vp, vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.mv_destroy.argtypes = [vp]
     lib.mv_destroy.restype = None
     lib.mv_last_error.restype = C.c_char_p
@@ -102,6 +106,25 @@ def _as_ptr(x) -> Optional[int]:
 
 def _is_device(x) -> bool:
     return bool(getattr(x, "is_cuda", False))
+
+
+class PinnedBuffer:
+    """Page-locked host memory from ``mv_host_alloc``; ``array(dtype, shape)`` views it as a NumPy array."""
+
+    def __init__(self, nbytes: int):
+        ptr = C.c_void_p()
+        _check(load_library().mv_host_alloc(C.byref(ptr), nbytes))
+        self.address, self.nbytes = ptr.value, nbytes
+
+    def array(self, dtype, shape):
+        import numpy as np
+        buf = (C.c_uint8 * self.nbytes).from_address(self.address)
+        return np.frombuffer(buf, dtype=dtype, count=int(np.prod(shape))).reshape(shape)
+
+    def close(self) -> None:
+        if self.address:
+            load_library().mv_host_free(self.address)
+            self.address = 0
 
 
 class Batch:
@@ -179,6 +202,13 @@ class Batch:
         bar.empty_rgb[:] = [int(v) for v in empty_rgb]
         _check(load_library().mv_draw_bars(self._h, _as_ptr(rgb), _as_ptr(fraction), C.byref(bar),
                                            1 if _is_device(fraction) else 0, stream))
+
+    def fetch_observations(self, rgb_dev, depth_dev, first_obs: int, count: int, rgb_host, depth_host,
+                           stream: int = 0) -> None:
+        """Enqueue the device-to-host copy of a range of observations; host arguments are NumPy arrays,
+        ``PinnedBuffer.address`` integers or None."""
+        _check(load_library().mv_fetch_observations(self._h, _as_ptr(rgb_dev), _as_ptr(depth_dev), first_obs, count,
+                                                    _as_ptr(rgb_host), _as_ptr(depth_host), stream))
 
     def debug_occupancy(self, env: int):
         """(x_rows_ptr, x_row_words, y_rows_ptr, y_row_words, top_layer_ptr) of one environment."""

@@ -414,6 +414,43 @@ int mv_draw_bars(mv_batch* b, uint8_t* rgb, const float* fraction, const mv_bar*
     return MV_OK;
 }
 
+int mv_host_alloc(void** out, size_t bytes)
+{
+    if (!out || bytes == 0) return fail(MV_ERR_ARG, "mv_host_alloc: null pointer or zero size");
+    void* ptr = nullptr;
+    MV_HIP(hipHostMalloc(&ptr, bytes, hipHostMallocDefault));
+    *out = ptr;
+    return MV_OK;
+}
+
+void mv_host_free(void* ptr)
+{
+    if (ptr) (void)hipHostFree(ptr);
+}
+
+int mv_fetch_observations(mv_batch* b, const uint8_t* rgb_dev, const float* depth_dev, int32_t first_obs, int32_t count,
+                          uint8_t* rgb_host, float* depth_host, void* hip_stream)
+{
+    if (!b) return fail(MV_ERR_ARG, "mv_fetch_observations: null batch");
+    if ((rgb_host && !rgb_dev) || (depth_host && !depth_dev))
+        return fail(MV_ERR_ARG, "mv_fetch_observations: a host destination needs its device tensor");
+    if (count <= 0) return fail(MV_ERR_ARG, "mv_fetch_observations: count must be positive");
+    if (first_obs < 0 || first_obs > b->num_obs - count)
+        return fail(MV_ERR_RANGE, "mv_fetch_observations: observations %d..%d outside 0..%d", first_obs,
+                    first_obs + count - 1, b->num_obs - 1);
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_fetch_observations: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t pixels = (size_t)b->cfg.width * (size_t)b->cfg.height;
+    if (rgb_host)
+        MV_HIP(hipMemcpyAsync(rgb_host, rgb_dev + (size_t)first_obs * pixels * 3, (size_t)count * pixels * 3,
+                              hipMemcpyDeviceToHost, stream));
+    if (depth_host)
+        MV_HIP(hipMemcpyAsync(depth_host, depth_dev + (size_t)first_obs * pixels, (size_t)count * pixels * 4,
+                              hipMemcpyDeviceToHost, stream));
+    return MV_OK;
+}
+
 void mv_destroy(mv_batch* b)
 {
     if (!b) return;

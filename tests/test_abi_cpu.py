@@ -92,6 +92,11 @@ def test_null_arguments(lib):
     assert lib.mv_upload_worlds(None, 0, 1, None, None, 0, None) == binding.MV_ERR_ARG
     assert lib.mv_set_cameras(None, None, None, 0, None) == binding.MV_ERR_ARG
     assert lib.mv_render_batch(None, None, None, None, None, None, None) == binding.MV_ERR_ARG
+    assert lib.mv_fetch_observations(None, None, None, 0, 1, None, None, None) == binding.MV_ERR_ARG
+    assert lib.mv_host_alloc(None, 16) == binding.MV_ERR_ARG
+    out = C.c_void_p()
+    assert lib.mv_host_alloc(C.byref(out), 0) == binding.MV_ERR_ARG
+    lib.mv_host_free(None)                                  # NULL-safe
     lib.mv_destroy(None)                                    # NULL-safe
     lib.mv_default_config(None)
 

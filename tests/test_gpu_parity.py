@@ -434,6 +434,36 @@ def test_largest_grid_the_lds_plan_takes(lib, orc):
     parity.compare(run.numpy(), ob.render(threads=4), label="128x128x32 grid")
 
 
+def test_fetch_observations_into_pinned_and_pageable_memory(lib):
+    """The device-to-host copy of a range of observations equals what the device tensors hold, for pinned
+    memory from the library and for ordinary NumPy arrays, and rejects ranges outside the batch."""
+    wl = synth.generate(1, num_envs=8)
+    spec = wl.spec
+    run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0], aux=False)
+    run.render()
+    H, W = spec.height, spec.width
+    first, count = 5, 19
+    pin_rgb = binding.PinnedBuffer(count * H * W * 3)
+    pin_depth = binding.PinnedBuffer(count * H * W * 4)
+    try:
+        run.batch.fetch_observations(run.rgb, run.depth, first, count, pin_rgb.address, pin_depth.address, stream=_stream())
+        page_rgb = np.zeros((count, H, W, 3), np.uint8)
+        run.batch.fetch_observations(run.rgb, None, first, count, page_rgb, None, stream=_stream())
+        torch.cuda.synchronize()
+        want_rgb = run.rgb[first:first + count].cpu().numpy()
+        want_depth = run.depth[first:first + count].cpu().numpy()
+        assert np.array_equal(pin_rgb.array(np.uint8, (count, H, W, 3)), want_rgb)
+        assert np.array_equal(pin_depth.array(np.float32, (count, H, W)).view(np.uint32), want_depth.view(np.uint32))
+        assert np.array_equal(page_rgb, want_rgb)
+        with pytest.raises(binding.MvError):
+            run.batch.fetch_observations(run.rgb, run.depth, spec.num_obs - 3, 4, pin_rgb.address, None, stream=_stream())
+        with pytest.raises(binding.MvError):
+            run.batch.fetch_observations(None, run.depth, 0, 1, pin_rgb.address, None, stream=_stream())
+    finally:
+        torch.cuda.synchronize()
+        pin_rgb.close(); pin_depth.close()
+
+
 def test_active_mask_and_indicator_bars(lib, orc):
     """Inactive environments are neither rendered nor painted (their pixels keep what the caller's
     tensors held); active ones are bit for bit what a full render gives; bars match the oracle."""
