@@ -325,9 +325,12 @@ static void trace_pixel(const mvo_batch* b, int32_t obs, int32_t row, int32_t co
         t_hit = t_max[axis];
         cell[axis] += step[axis];
         out->steps += 1;
-        if (cell[axis] < 0 || cell[axis] >= dim[axis]) return;          /* left the grid: miss */
+        /* every plane crossing counts for the margin, the one through the grid boundary included: a ray
+           that leaves within a hair of the line where the boundary meets a voxel face is as much a tie
+           (leave, or enter that voxel) as one that grazes an edge inside the grid */
         double m = crossing_margin(P, d, t_hit, axis);
         if (m < out->edge_margin) out->edge_margin = m;
+        if (cell[axis] < 0 || cell[axis] >= dim[axis]) return;          /* left the grid: miss */
         double next_plane = (double)(cell[axis] + (step[axis] > 0 ? 1 : 0));
         t_max[axis] = (next_plane - P[axis]) / d[axis];
         face = 2 * axis + (step[axis] < 0 ? 1 : 0);

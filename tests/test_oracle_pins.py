@@ -549,3 +549,28 @@ def test_pitched_camera_floor_landing_points(orc):
     assert (out.face[0][sure] == 5).all()
     clear_miss = ~down | (~inside & (np.abs(land[..., :2] - 20).max(axis=-1) > 20.01))
     assert (out.hit_index[0][clear_miss] == -1).all()
+
+
+def test_edge_margin_flags_ties_at_the_grid_boundary(orc):
+    """The margin side channel must mark a ray as a tie wherever its fate hangs on rounding: also when the
+    choice is between leaving the grid and entering the last voxel before the boundary.  A 1x1 image looks
+    along yaw exactly (sx = sy = 0); the ray from (6.5, 3.5) towards the corner (8, 6) either leaves through
+    x = 8 or enters voxel (7, 6) through y = 6.  Slightly turned either way it does one or the other, and
+    both times it passes the corner within 5e-5: the margin must say so.  A ray aimed well away from the
+    corner must keep a large margin."""
+    grid = (8, 8, 4)
+    vox = np.zeros((4, 8, 8), np.uint8)
+    vox[1, 6, 7] = 1
+    pal = np.full((2, 3), 100, np.uint8)
+    yaw = np.arctan2(2.5, 1.5)
+    cams = np.array([[6.5, 3.5, 1.5, yaw - 2e-6, 0.0], [6.5, 3.5, 1.5, yaw + 2e-6, 0.0],
+                     [6.5, 3.5, 1.5, yaw - 0.2, 0.0], [6.5, 3.5, 1.5, yaw + 0.1, 0.0]], np.float32)
+    b = orc.OracleBatch(1, 4, grid, 1, 1, 1)
+    b.upload_worlds(vox[None], pal[None])
+    b.set_cameras(cams)
+    out = b.render()
+    hit = out.hit_index[:, 0, 0]
+    assert hit[0] == -1 and hit[1] == (1 * 8 + 6) * 8 + 7, hit          # one leaves, one enters
+    assert out.edge_margin[0, 0, 0] < 5e-5 and out.edge_margin[1, 0, 0] < 5e-5
+    assert hit[2] == -1 and out.edge_margin[2, 0, 0] > 0.01             # clear miss
+    assert hit[3] == (1 * 8 + 6) * 8 + 7 and out.edge_margin[3, 0, 0] > 0.01   # clear hit
