@@ -328,7 +328,9 @@ def _mini_spec(N, A, grid, W, H, M):
 
 @pytest.mark.parametrize("grid,W,H", [((7, 5, 3), 33, 19), ((1, 1, 1), 1, 1), ((8, 8, 4), 2, 2), ((5, 9, 2), 30, 17),
                                       ((40, 40, 16), 130, 70), ((33, 2, 31), 64, 8), ((70, 9, 5), 40, 24),
-                                      ((64, 64, 6), 48, 32), ((9, 100, 4), 36, 20)])
+                                      ((64, 64, 6), 48, 32), ((9, 100, 4), 36, 20), ((63, 64, 3), 40, 24),
+                                      ((64, 1, 2), 16, 16), ((1, 64, 2), 24, 8), ((17, 63, 9), 128, 72),
+                                      ((64, 64, 40), 64, 40), ((64, 64, 76), 32, 24)])
 def test_unstructured_worlds_odd_sizes_cameras_anywhere(lib, orc, grid, W, H):
     """Random occupancy (overhangs, no floor), cameras inside, outside and inside solids, image sizes
     that are not multiples of the tile or of four, grids whose voxel count is not a multiple of 32."""
@@ -351,6 +353,17 @@ def test_unstructured_worlds_odd_sizes_cameras_anywhere(lib, orc, grid, W, H):
             assert (np.abs(g.rgb.astype(int) - ref.rgb.astype(int)).max(axis=-1)[same] <= 1).all()
             np.testing.assert_allclose(g.depth[same], ref.depth[same], rtol=1e-4, atol=0)
             assert differ.mean() <= 0.002
+
+
+@pytest.mark.parametrize("hfov", [0.2, 1.0, 2.6, 3.0])
+def test_narrow_and_wide_fields_of_view(lib, orc, hfov):
+    """Horizontal fields of view from 11 to 172 degrees on an arena world: parity at every pixel."""
+    wl = synth.generate(1, num_envs=6)
+    spec = wl.spec
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0], hfov_rad=hfov)
+    run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0], hfov_rad=hfov)
+    run.render()
+    parity.compare(run.numpy(), ob.render(threads=8), label=f"hfov {hfov}")
 
 
 def test_axis_parallel_and_vertical_rays(lib, orc):
