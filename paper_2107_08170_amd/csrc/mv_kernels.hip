@@ -784,6 +784,10 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         c.Pu = neg ? (float)U - pu : pu;
         c.uexit = (float)U - c.Pu;
         c.i0 = min(max((int)floorf(c.Pu), 0), U - 1);
+        // A camera exactly on a u plane belongs to the cell on the + side (cell = floor(P)).  In mirrored
+        // coordinates that cell is the one before floor(Pu): start the scan there, so that the neighbour
+        // on the - side is found as an ordinary hit along the row (through its u face, at t = 0).
+        if (neg && c.Pu == floorf(c.Pu) && c.i0 >= 1 && c.Pu < (float)U) c.i0 -= 1;
         const int j0 = min(max((int)floorf(pv), 0), V - 1);
         c.hi_v = (float)(j0 + 1) - pv;
         c.lo_v = (float)j0 - pv;

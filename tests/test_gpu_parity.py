@@ -366,6 +366,35 @@ def test_narrow_and_wide_fields_of_view(lib, orc, hfov):
     parity.compare(run.numpy(), ob.render(threads=8), label=f"hfov {hfov}")
 
 
+def test_cameras_exactly_on_voxel_planes(lib, orc):
+    """Cameras whose x, y or z is an integer sit on a voxel plane: the cell is floor(P), and a solid
+    neighbour across the plane is hit at depth 0 through that plane's face.  One integer coordinate is not
+    a tie (the margin looks at the other two axes), so these pixels must match exactly."""
+    grid = (9, 7, 5)
+    rng = np.random.default_rng(77)
+    N, A, M = 6, 6, 9
+    spec = _mini_spec(N, A, grid, 40, 24, M)
+    vox, pal = synth.random_world(rng, N, grid, 0.35, M)
+    cams = synth.random_cameras(rng, N * A, grid, margin=0.0)
+    cams[:, 0] = np.clip(cams[:, 0], 0.2, grid[0] - 0.2)
+    cams[:, 1] = np.clip(cams[:, 1], 0.2, grid[1] - 0.2)
+    cams[:, 2] = np.clip(cams[:, 2], 0.2, grid[2] - 0.2)
+    for o in range(N * A):
+        axis = o % 3
+        cams[o, axis] = float(rng.integers(1, grid[axis]))      # on an interior plane of that axis
+    ob = _oracle_for(orc, spec, vox, pal, cams)
+    ref = ob.render()
+    run = _gpu_for(spec, vox, pal, cams)
+    run.render()
+    g = run.numpy()
+    differ = (g.hit_index != ref.hit_index) | (g.material != ref.material) | (g.face != ref.face)
+    assert not (differ & ~(ref.edge_margin < parity.EDGE_MARGIN)).any()
+    same = ~differ
+    assert (np.abs(g.rgb.astype(int) - ref.rgb.astype(int)).max(axis=-1)[same] <= 1).all()
+    np.testing.assert_allclose(g.depth[same], ref.depth[same], rtol=1e-4, atol=0)
+    assert ((ref.depth == 0) & (ref.hit_index >= 0) & (ref.face < 6)).any(), "some pixel hits a neighbour at depth 0"
+
+
 def test_axis_parallel_and_vertical_rays(lib, orc):
     grid = (6, 6, 6)
     vox = np.zeros((1, 6, 6, 6), np.uint8)
