@@ -381,7 +381,8 @@ def test_cameras_exactly_on_voxel_planes(lib, orc):
     cams[:, 2] = np.clip(cams[:, 2], 0.2, grid[2] - 0.2)
     for o in range(N * A):
         axis = o % 3
-        cams[o, axis] = float(rng.integers(1, grid[axis]))      # on an interior plane of that axis
+        # on an interior plane of that axis, or (every fourth camera) on the grid boundary itself
+        cams[o, axis] = float(rng.integers(1, grid[axis])) if o % 4 else float(rng.choice([0, grid[axis]]))
     ob = _oracle_for(orc, spec, vox, pal, cams)
     ref = ob.render()
     run = _gpu_for(spec, vox, pal, cams)
