@@ -48,16 +48,17 @@ def algorithmic_bytes_per_obs(spec) -> float:
     return rays * 7 + rays * 1 + (occ_bytes + lut_bytes) / spec.agents_per_env + 64
 
 
-def measured_traffic(workload: str):
-    """HBM bytes per render launch from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE
-    scaled against a plain copy), or None when no summary covers this workload."""
+def measured_traffic(workload: str, column: int = 1):
+    """Bytes per render launch from the committed rocprofv3 counter summary: column 1 = HBM (FETCH_SIZE and
+    WRITE_SIZE scaled against a plain copy), column 2 = LDS (from SQ_INSTS_LDS); None when no summary covers
+    this workload."""
     path = os.path.join(ROOT, "profiles", "render_traffic.txt")
     try:
         with open(path) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) >= 2 and parts[0] == workload:
-                    return float(parts[1])
+                if len(parts) > column and parts[0] == workload:
+                    return float(parts[column])
     except OSError:
         pass
     return None
@@ -207,7 +208,7 @@ def main() -> int:
     achieved = alg_bytes / (render_ms.mean() * 1e-3) / 1e9
 
     result = {
-        "metric": "egocentric observations/sec (128x72 RGB+depth) on 1 MI355X",
+        "metric": "egocentric observations/sec (128\u00d772 RGB+depth) on 1 MI355X; % of HBM peak",
         "value": obs_per_s,
         "unit": "observations/s",
         "n_gpus": 1,
@@ -230,6 +231,7 @@ def main() -> int:
         "render_kernel_ms": {"mean": float(render_ms.mean()), "median": float(np.median(render_ms)),
                              "p95": float(np.percentile(render_ms, 95))},
         "render_only_obs_per_s": n / (render_ms.mean() * 1e-3),
+        "hbm_peak_fraction": achieved / HBM_PEAK_GBS,
         "generator_seconds": gen_s,
         "input_sha256": input_digest(wl),
     }
@@ -247,6 +249,14 @@ def main() -> int:
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                               "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
                               "device_copy_GBs": device_copy_rate(torch)}
+    lds_bytes = measured_traffic(spec.name, 2)
+    if lds_bytes is not None:
+        # LDS peak: 256 CUs x 128 bytes per clock x 2.4 GHz
+        lds_peak = 256 * 128 * 2.4
+        result["lds_roofline"] = {"bound": "lds", "kernel": "mv::render_kernel",
+                                  "achieved": lds_bytes / (render_ms.mean() * 1e-3) / 1e9, "peak": lds_peak,
+                                  "unit": "GB/s", "frac": lds_bytes / (render_ms.mean() * 1e-3) / 1e9 / lds_peak,
+                                  "bytes_per_launch": lds_bytes}
 
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
