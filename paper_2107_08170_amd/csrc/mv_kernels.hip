@@ -65,9 +65,13 @@ LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one)
     const LdsMap m = lds_map(g, W, H, materials_plus_one);
     if (m.total > kLdsBudget) return plan;                                  // bytes == 0: does not fit
     plan.bytes = m.total;
-    // keep at least ~16 waves resident per CU whatever one workgroup's LDS share is
+    // as many waves per workgroup as fill the CU's wave slots with the workgroups its LDS can hold
+    // (measured: 64x64x32 grids, two workgroups per CU: 1024 threads render 9 % faster than 512)
     size_t per_cu = kLdsBudget / plan.bytes;
-    plan.threads = per_cu >= 4 ? 256 : (per_cu >= 2 ? 512 : 1024);
+    size_t waves = 32 / (per_cu < 1 ? 1 : per_cu);          // 32 wave slots per CU
+    if (waves < 4) waves = 4;
+    if (waves > 16) waves = 16;
+    plan.threads = (int)(waves * 64);
     return plan;
 }
 
@@ -173,8 +177,9 @@ __device__ __forceinline__ uint64_t transpose_bits_across_lanes(uint64_t row, in
     return ((uint64_t)hi << 32) | lo;
 }
 
-constexpr int kPackPrefetch = 8;           // dwords of the next layer each lane keeps in flight
-
+// kPackPrefetch = dwords of the next layer each lane keeps in flight: 8 covers layers up to 2 KiB (40x40), 16
+// layers up to 4 KiB (64x64); the deeper variant costs registers, so small layers keep the shallow one.
+template <int kPackPrefetch>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
                                                             uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
                                                             GridLayout g, int vec_ok, const uint8_t* __restrict__ pal_src,
@@ -316,8 +321,12 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
     const size_t lds = layer_stride * (kPackThreads / 64);
     const int vec_ok = (XY % 4 == 0) && ((reinterpret_cast<uintptr_t>(src) & 3) == 0) &&
                        ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
-    hipLaunchKernelGGL(pack_kernel, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst, g,
-                       vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
+    if (XY / 4 <= 8 * 64)
+        hipLaunchKernelGGL(pack_kernel<8>, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
+                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
+    else
+        hipLaunchKernelGGL(pack_kernel<16>, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
+                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
     return hipGetLastError();
 }
 
