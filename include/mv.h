@@ -27,7 +27,11 @@
  * mv_last_error() returns a thread-local, NUL-terminated description of the last failure on
  * the calling thread.  Work is enqueued on the caller's HIP stream and the calls return without
  * synchronising; ordering between calls is stream order.  A batch must not be used from two
- * threads at once.
+ * threads at once, and calls that touch the same batch from different streams must be ordered
+ * by the caller (events or synchronisation): the batch's device buffers carry no locks.  Calls
+ * that take host memory (src_is_device == 0) validate it, copy it and wait for the copy, so
+ * they return only when the stream has passed them; the device-memory forms never wait and
+ * allocate nothing, which makes a step built from them capturable in a HIP graph.
  */
 #ifndef MV_H
 #define MV_H
