@@ -616,10 +616,10 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const float inv_z = safe_rcp(dz);
     const float dt_v = fabsf(inv_v), dt_z = fabsf(inv_z);
     const bool vneg = dv < 0.0f, zneg = dz < 0.0f;
-    // first crossing on an axis: (upper plane - P)/d if d > 0, (lower plane - P)/d otherwise; the other
-    // candidate is <= 0, so the maximum picks the right one without a compare
-    const float t0_v = vmax(c.hi_v * inv_v, c.lo_v * inv_v);
-    const float t0_z = vmax(hi_z * inv_z, lo_z * inv_z);
+    // first crossing on an axis: (upper plane - P)/d if d > 0, (lower plane - P)/d otherwise: the distance
+    // to that plane (hi >= 0 >= lo) times |1/d|; d = -0 counts as positive, its reciprocal is +-huge either way
+    const float t0_v = fabsf(vneg ? c.lo_v : c.hi_v) * dt_v;
+    const float t0_z = fabsf(zneg ? lo_z : hi_z) * dt_z;
     // leaving the grid: same |n|*dt + t0 expression as the crossings, so the comparison below is exact
     const float t_end = vmin3(c.uexit * inv_u, fmaf(vneg ? c.nv_neg : c.nv_pos, dt_v, t0_v),
                               fmaf(zneg ? nz_neg : nz_pos, dt_z, t0_z));
@@ -663,10 +663,11 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     // in_range is r moved up so that cell i_last sits at bit 63: its lowest set bit p is cell i_last - (63 - p)
     const int iu = i_last - 63 + ctz64_nonzero(in_range);                        // mirrored cell along u
     const bool along_row = ((uint32_t)r & 1u) == 0u;                            // not the row's entry cell
-    // the row was entered at the later of the last v crossing and the last z crossing (|n|-1; for n = 0
-    // the expression is <= 0 because the first plane is at most one cell away)
-    const float tv_last = fmaf(fabsf(n_v) - 1.0f, dt_v, t0_v);
-    const float tz_last = fmaf(fabsf(n_z) - 1.0f, dt_z, t0_z);
+    // the row was entered at the later of the last v crossing and the last z crossing: one step before the
+    // next ones, which the loop left in t_v and t_z (for n = 0 the result is <= 0: the first plane is at most
+    // one cell away)
+    const float tv_last = t_v - dt_v;
+    const float tz_last = t_z - dt_z;
     const bool via_z = tz_last >= tv_last;
     // A hit in the row's entry cell was entered through the later of the two crossings.  The camera's own
     // cell is never solid here (the caller handles that camera before tracing), so the only way to find
