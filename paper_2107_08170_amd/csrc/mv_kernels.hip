@@ -94,9 +94,11 @@ hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t 
 
 // ------------------------------------------------------------------------------------------
 // pack: one workgroup per environment.  Each wave takes whole z layers: the layer's material bytes
-// go through LDS (dword global reads, and the copy into the batch's own grid); then lane r builds
-// bit row r by walking along it (two vector operations per cell for 64 rows at once), first the
-// rows along x, then the rows along y, and the rows leave as one coalesced store per 64 rows.
+// are prefetched into registers one layer ahead, go through LDS and leave again as the batch's own
+// copy.  Grids of one word per row (X, Y <= 64, X a multiple of 4): lane j turns x row j into bits
+// dword by dword (non-zero bytes -> nibble with a carry trick and one dot product), and the y rows
+// are the 64x64 bit transpose of the x rows, done across lanes without memory.  Other grids: lane r
+// gathers row r cell by cell.  Rows leave as one coalesced store per 64 rows.
 // ------------------------------------------------------------------------------------------
 constexpr int kPackThreads = 256;
 
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     if (threadIdx.x == 0) top_lds = 0;
     __syncthreads();
     int top = 0;
-    // a layer of up to 8*64 dwords (2 KiB) is prefetched into registers while the previous one is packed
+    // a layer of up to kPackPrefetch*64 dwords is prefetched into registers while the previous one is packed
     const int n4 = XY >> 2;
     const bool prefetch = vec_ok && n4 <= kPackPrefetch * 64;
     const bool quick = g.fast && (X & 3) == 0 && XY >= 8 * Y;     // the x rows (8 B each) fit over the layer in LDS
