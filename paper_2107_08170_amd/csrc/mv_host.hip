@@ -350,8 +350,10 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     int tpb = b->cfg.tiles_per_block;
     if (tpb <= 0) {
         // Enough workgroups to fill 256 CUs several times over, but no more re-staging of the
-        // grid than needed: whole observations per block for large batches, strips otherwise.
-        const long long target_blocks = 256ll * 32;
+        // grid than needed: whole observations per block for large batches, strips otherwise
+        // (measured on 1024 observations of 40x40x16 worlds: 6 strips per observation, 6144
+        // workgroups, render 6 % faster than 8 strips and 23 % faster than whole observations).
+        const long long target_blocks = 256ll * 24;
         long long per_obs = (target_blocks + b->num_obs - 1) / b->num_obs;
         if (per_obs < 1) per_obs = 1;
         tpb = (int)((p.tiles_per_obs + per_obs - 1) / per_obs);
