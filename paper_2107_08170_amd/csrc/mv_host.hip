@@ -349,15 +349,23 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.tiles_per_obs = p.tiles_x * tiles_y;
     int tpb = b->cfg.tiles_per_block;
     if (tpb <= 0) {
-        // Enough workgroups to fill 256 CUs several times over, but no more re-staging of the
-        // grid than needed: whole observations per block for large batches, strips otherwise
-        // (measured on 1024 observations of 40x40x16 worlds: 6 strips per observation, 6144
-        // workgroups, render 6 % faster than 8 strips and 23 % faster than whole observations).
+        // Strips of an observation per workgroup.  Two pulls: (1) enough workgroups to fill 256 CUs a few
+        // times over (about 6144: on 1024 observations of 40x40x16 worlds, 6 strips per observation render
+        // 6 % faster than 8 and 23 % faster than whole observations); (2) when a CU holds four or more
+        // workgroups, so that one workgroup's staging hides behind the others' tracing, about 12 tiles per
+        // wave balance the tail best (3 strips of 48 tiles: 5 % faster than 2 on the dynamic workload,
+        // neutral on the benchmark workload).  Grids that leave room for only two workgroups per CU render
+        // whole observations: every strip would re-stage 67 KB with nothing to hide it (-9 % when split).
+        const int waves = p.threads / 64;
         const long long target_blocks = 256ll * 24;
-        long long per_obs = (target_blocks + b->num_obs - 1) / b->num_obs;
-        if (per_obs < 1) per_obs = 1;
-        tpb = (int)((p.tiles_per_obs + per_obs - 1) / per_obs);
-        const int min_tpb = (p.threads / 64) * 2;
+        long long strips = (target_blocks + b->num_obs - 1) / b->num_obs;
+        if (mv::kLdsBudget / b->plan.bytes >= 4) {
+            const long long balanced = (p.tiles_per_obs + 12 * waves - 1) / (12 * waves);
+            if (balanced > strips) strips = balanced;
+        }
+        if (strips < 1) strips = 1;
+        tpb = (int)((p.tiles_per_obs + strips - 1) / strips);
+        const int min_tpb = waves * 2;
         if (tpb < min_tpb) tpb = min_tpb;
     }
     if (tpb > p.tiles_per_obs) tpb = p.tiles_per_obs;
