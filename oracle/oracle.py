@@ -147,7 +147,11 @@ class OracleBatch:
             _load().mvo_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: module globals may already be gone
+            pass
 
     def upload_worlds(self, voxels: np.ndarray, palette: Optional[np.ndarray], first_env: int = 0):
         X, Y, Z = self.grid
