@@ -633,7 +633,8 @@ def _read_device(ptr, nbytes):
     return buf
 
 
-@pytest.mark.parametrize("grid", [(40, 40, 16), (7, 5, 3), (16, 16, 8), (64, 64, 4), (70, 3, 5), (3, 130, 2)])
+@pytest.mark.parametrize("grid", [(40, 40, 16), (7, 5, 3), (16, 16, 8), (64, 64, 4), (70, 3, 5), (3, 130, 2), (64, 64, 9),
+                                  (48, 56, 10), (36, 20, 7)])
 def test_pack_kernel_bit_exact(lib, grid):
     """Occupancy bit rows along x and along y, and the top solid layer, against NumPy."""
     rng = np.random.default_rng(17)
