@@ -35,7 +35,7 @@ GridLayout make_layout(int X, int Y, int Z)
 
 static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
-// LDS map (bytes):  [4 scan-class records, 64 B each] | [sx: W floats][sy: H floats] |
+// LDS map (bytes):  [4 scan-class records, 80 B each] | [sx: W floats][sy: H floats] |
 //                   [colour table 7*(M+1) dwords] | bit rows
 // fast grids stage four row arrays (x, x mirrored, y, y mirrored); others stage the x rows only.
 struct LdsMap {
@@ -47,7 +47,7 @@ static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one)
 {
     LdsMap m{};
     size_t off = 0;
-    m.classes = (uint32_t)off; off += 4 * 64;
+    m.classes = (uint32_t)off; off += 4 * 80;
     m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
     m.lut = (uint32_t)off;
     off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
@@ -445,8 +445,10 @@ struct alignas(16) ScanClass {
     int   stride_u;     // voxel-index step per mirrored u cell: +-1 (x scans) or +-X (y scans)
     int   stride_v;     // voxel-index step per v cell: X (x scans) or 1 (y scans)
     int   zstride_neg;  // -zstride
+    float Pu_err;       // what rounding took from the mirrored coordinate: (U - P) - Pu exactly, 0 if not mirrored
+    int   pad[3];
 };
-static_assert(sizeof(ScanClass) == 64, "scan class record must be 64 bytes");
+static_assert(sizeof(ScanClass) == 80, "scan class record must be 80 bytes");
 
 // Plain 3D-DDA through the x rows (any row width).  Used for cameras outside the grid and for grids
 // wider than 64 voxels.  Crossing parameters are t = n*|1/d| + t_first (one fused op, error relative
@@ -602,14 +604,14 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
     const float dv = xm ? dy : dx;
-    // class = 2*(y dominant) + (direction negative); its record sits at 64*class from the start of the
+    // class = 2*(y dominant) + (direction negative); its record sits at 80*class from the start of the
     // workgroup's dynamic LDS
-    const uint32_t qoff = (xm ? 0u : 128u) | ((__float_as_uint(du) >> 31) << 6);
+    const uint32_t qoff = (xm ? 0u : 160u) + (__float_as_uint(du) >> 31) * 80u;
     ScanClass c;
     {
         lds_u32x4_ptr rec = (lds_u32x4_ptr)(uintptr_t)(classes_addr + qoff);
         u32x4* dst = reinterpret_cast<u32x4*>(&c);
-        dst[0] = rec[0]; dst[1] = rec[1]; dst[2] = rec[2]; dst[3] = rec[3];
+        dst[0] = rec[0]; dst[1] = rec[1]; dst[2] = rec[2]; dst[3] = rec[3]; dst[4] = rec[4];
     }
 
     const float dua = fabsf(du);
@@ -665,18 +667,20 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     // in_range is r moved up so that cell i_last sits at bit 63: its lowest set bit p is cell i_last - (63 - p)
     const int iu = i_last - 63 + ctz64_nonzero(in_range);                        // mirrored cell along u
     const bool along_row = ((uint32_t)r & 1u) == 0u;                            // not the row's entry cell
-    // the row was entered at the later of the last v crossing and the last z crossing: one step before the
-    // next ones, which the loop left in t_v and t_z (for n = 0 the result is <= 0: the first plane is at most
-    // one cell away)
-    const float tv_last = t_v - dt_v;
-    const float tz_last = t_z - dt_z;
+    // the row was entered at the later of the last v crossing and the last z crossing (|n|-1; for n = 0
+    // the expression is <= 0 because the first plane is at most one cell away).  Recomputed with one
+    // fused operation each: "t_v - dt_v" would cancel badly for a camera that almost touches a plane.
+    const float tv_last = fmaf(fabsf(n_v) - 1.0f, dt_v, t0_v);
+    const float tz_last = fmaf(fabsf(n_z) - 1.0f, dt_z, t0_z);
     const bool via_z = tz_last >= tv_last;
     // A hit in the row's entry cell was entered through the later of the two crossings.  The camera's own
     // cell is never solid here (the caller handles that camera before tracing), so the only way to find
     // the entry cell of the first row solid is a camera exactly on a cell boundary looking into the
     // neighbour: both crossings are <= 0 then and the hit is at t = 0 on that boundary.
     const float t_in = vmax3(tv_last, tz_last, 0.0f);
-    const float t_u = ((float)iu - c.Pu) * inv_u;
+    // distance along u to the near face of the hit cell: the mirrored camera coordinate was rounded once,
+    // which matters when the camera almost touches that face; its exact rounding error comes with the class
+    const float t_u = (((float)iu - c.Pu) - c.Pu_err) * inv_u;
     const int face_vz = via_z ? (zneg ? 5 : 4) : c.face_v + (vneg ? 1 : 0);
     const int face = along_row ? c.face_u : face_vz;
     const float t = along_row ? t_u : t_in;
@@ -719,7 +723,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
 
     // LDS map, mirrors lds_map() on the host
     const uint32_t off_classes = 0;
-    const uint32_t off_scalars = 256;
+    const uint32_t off_scalars = 320;
     const uint32_t off_lut = off_scalars + (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
     const uint32_t off_rows = off_lut + (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15);
     float* lds_sx = reinterpret_cast<float*>(lds + off_scalars);
@@ -794,6 +798,13 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         const float pu = xmaj ? P[0] : P[1], pv = xmaj ? P[1] : P[0];
         ScanClass c;
         c.Pu = neg ? (float)U - pu : pu;
+        c.Pu_err = 0.0f;
+        c.pad[0] = c.pad[1] = c.pad[2] = 0;
+        if (neg) {                                         // exact error of the rounded difference (two-sum)
+            const float a = (float)U, bneg = -pu;
+            const float bb = __fsub_rn(c.Pu, a);
+            c.Pu_err = __fadd_rn(__fsub_rn(a, __fsub_rn(c.Pu, bb)), __fsub_rn(bneg, bb));
+        }
         c.uexit = (float)U - c.Pu;
         c.i0 = min(max((int)floorf(c.Pu), 0), U - 1);
         // A camera exactly on a u plane belongs to the cell on the + side (cell = floor(P)).  In mirrored
@@ -817,7 +828,7 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         c.stride_v = xmaj ? X : 1;
         c.idx0 = k0 * X * Y + j0 * c.stride_v + (neg ? (U - 1) * su : 0);
         c.zstride_neg = -8 * V;
-        *reinterpret_cast<ScanClass*>(lds + off_classes + q * 64) = c;
+        *reinterpret_cast<ScanClass*>(lds + off_classes + q * 80) = c;
     }
     __syncthreads();
 
