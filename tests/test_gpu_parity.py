@@ -452,16 +452,87 @@ def test_randomized_configurations_against_the_oracle(lib, orc):
         run = GpuRun(batch, W, H, aux=True)
         run.render()
         g = run.numpy()
-        differ = (g.hit_index != ref.hit_index) | (g.material != ref.material) | (g.face != ref.face)
-        where = f"seed {seed} grid {grid} image {W}x{H}"
-        assert not (differ & ~(ref.edge_margin < parity.EDGE_MARGIN)).any(), where
-        same = ~differ
-        assert (np.abs(g.rgb.astype(int) - ref.rgb.astype(int)).max(axis=-1)[same] <= 1).all(), where
-        assert (np.abs(g.depth - ref.depth)[same] <= 1e-4 * np.abs(ref.depth)[same]).all(), where
-        pixels += differ.size
+        _pixelwise_rule(g, ref, f"seed {seed} grid {grid} image {W}x{H}")
+        pixels += g.depth.size
         batch.close()
         ob.close()
     assert pixels > 5_000_000
+
+
+def _pixelwise_rule(g, ref, where):
+    differ = (g.hit_index != ref.hit_index) | (g.material != ref.material) | (g.face != ref.face)
+    assert not (differ & ~(ref.edge_margin < parity.EDGE_MARGIN)).any(), where
+    same = ~differ
+    assert (np.abs(g.rgb.astype(int) - ref.rgb.astype(int)).max(axis=-1)[same] <= 1).all(), where
+    assert (np.abs(g.depth - ref.depth)[same] <= 1e-4 * np.abs(ref.depth)[same]).all(), where
+
+
+def test_randomized_entry_point_sequences(lib, orc):
+    """300 random configurations driven through the other entry points: per-environment uploads in random
+    order from host or device memory, a random launch shape, the colour+depth-only launch against the one
+    with auxiliary outputs (bit for bit), random sparse edits (sets and clears) from host or device memory,
+    a random active mask, and a random indicator bar -- each step against the oracle."""
+    for seed in range(9000, 9300):
+        grid, W, H, N, A, M, vox, pal, cams, selfv, hfov = _random_configuration(seed)
+        rng = np.random.default_rng(seed + 10 ** 6)
+        X, Y, Z = grid
+        where = f"seed {seed} grid {grid} image {W}x{H}"
+        ob = orc.OracleBatch(N, A, grid, W, H, M, hfov_rad=hfov)
+        batch = binding.Batch(N, A, grid, M, W, H, hfov_rad=hfov, tiles_per_block=int(rng.choice([0, 1, 2, 3, 5, 8, 1000])))
+        for e in rng.permutation(N):
+            v, p_ = vox[e:e + 1], pal[e:e + 1]
+            if rng.random() < 0.5:
+                batch.upload_worlds(torch.from_numpy(v).cuda(), torch.from_numpy(p_).cuda(), first_env=int(e), stream=_stream())
+            else:
+                batch.upload_worlds(v, p_, first_env=int(e), stream=_stream())
+        torch.cuda.synchronize()
+        ob.upload_worlds(vox, pal)
+        batch.set_cameras(torch.from_numpy(cams).cuda(), None if selfv is None else torch.from_numpy(selfv).cuda(),
+                          stream=_stream())
+        ob.set_cameras(cams, selfv)
+        full = GpuRun(batch, W, H, aux=True)
+        full.render()
+        _pixelwise_rule(full.numpy(), ob.render(), where + " uploads")
+        plain = GpuRun(batch, W, H, aux=False)
+        plain.render()
+        assert torch.equal(plain.rgb, full.rgb) and torch.equal(plain.depth.view(torch.int32), full.depth.view(torch.int32)), where
+        # sparse edits, each voxel at most once
+        flat = rng.choice(N * X * Y * Z, size=min(int(rng.integers(1, 200)), N * X * Y * Z), replace=False)
+        env, idx = (flat // (X * Y * Z)).astype(np.int32), (flat % (X * Y * Z)).astype(np.int32)
+        mat = np.where(rng.random(env.size) < 0.5, 0, rng.integers(1, M + 1, size=env.size)).astype(np.uint8)
+        if rng.random() < 0.5:
+            batch.update_voxels(torch.from_numpy(env).cuda(), torch.from_numpy(idx).cuda(), torch.from_numpy(mat).cuda(),
+                                stream=_stream())
+        else:
+            batch.update_voxels(env, idx, mat, stream=_stream())
+        torch.cuda.synchronize()
+        ob.update_voxels(env, idx, mat)
+        full.render()
+        ref = ob.render()
+        _pixelwise_rule(full.numpy(), ref, where + " edits")
+        # active mask and bar
+        active = (rng.random(N) < 0.6).astype(np.uint8)
+        batch.set_active(torch.from_numpy(active).cuda() if rng.random() < 0.5 else active, stream=_stream())
+        rendered = full.rgb.cpu().numpy()
+        full.rgb.fill_(9); full.depth.fill_(-3.0)
+        batch.render(full.rgb, full.depth, full.material, full.hit, full.face, stream=_stream())
+        bw, bh = int(rng.integers(1, W + 1)), int(rng.integers(1, H + 1))
+        bx, by = int(rng.integers(0, W - bw + 1)), int(rng.integers(0, H - bh + 1))
+        frac = rng.uniform(-0.2, 1.2, size=N * A).astype(np.float32)
+        batch.draw_bars(full.rgb, torch.from_numpy(frac).cuda() if rng.random() < 0.5 else frac, bx, by, bw, bh,
+                        (255, 0, 0), (10, 20, 30), stream=_stream())
+        torch.cuda.synchronize()
+        want = ref.rgb.copy()
+        ob.draw_bars(want, frac, bx, by, bw, bh, (255, 0, 0), (10, 20, 30), active=active)
+        got, got_d = full.rgb.cpu().numpy(), full.depth.cpu().numpy()
+        on = np.repeat(active.astype(bool), A)
+        inside = np.zeros((H, W), bool)
+        inside[by:by + bh, bx:bx + bw] = True
+        assert (got[~on] == 9).all() and (got_d[~on] == -3.0).all(), where + ": inactive environments were touched"
+        assert (got[on][:, inside] == want[on][:, inside]).all(), where + ": bar pixels"
+        assert (got[on][:, ~inside] == rendered[on][:, ~inside]).all(), where + ": pixels outside the bar"
+        batch.close()
+        ob.close()
 
 
 def test_axis_parallel_and_vertical_rays(lib, orc):
