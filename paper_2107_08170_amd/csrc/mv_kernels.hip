@@ -69,7 +69,8 @@ LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one)
     // (measured: 64x64x32 grids, two workgroups per CU: 1024 threads render 9 % faster than 512)
     size_t per_cu = kLdsBudget / plan.bytes;
     size_t waves = 32 / (per_cu < 1 ? 1 : per_cu);          // 32 wave slots per CU
-    if (waves < 4) waves = 4;
+    waves &= ~(size_t)3;                                    // whole multiples of the 4 SIMDs: 5 or 6 waves per
+    if (waves < 4) waves = 4;                               // workgroup load the SIMDs unevenly (-10 % measured)
     if (waves > 16) waves = 16;
     plan.threads = (int)(waves * 64);
     return plan;
