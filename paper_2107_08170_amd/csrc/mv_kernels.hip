@@ -867,7 +867,51 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     const uint32_t last_voxel = (uint32_t)p.voxels_per_env - 1u;
     const int last_material = p.materials_plus_one - 1;
 
+    // a6 + a7 of a finished tile: material -> colour, then the stores.
+    auto shade_and_store = [&](int idx, int hit_face, float t, int material, uint32_t pix, bool active) {
+        // branch-free: lanes that found nothing look up a valid entry as well and then take the miss values
+        const bool hit = idx >= 0;
+        const uint32_t shaded = lut_lds[mad24s(min(hit_face, kNumFaces - 1), p.materials_plus_one, min(material, last_material))];
+        const uint32_t colour = hit ? shaded : p.sky_packed;
+        const float depth = hit ? t : 0.0f;
+        const int face = hit ? hit_face : 255;
+        material = hit ? material : 0;
+        if (active) {
+            depth_obs[pix] = depth;
+            if (AUX) {
+                if (auxm_obs) auxm_obs[pix] = (uint8_t)material;
+                if (auxh_obs) auxh_obs[pix] = idx;
+                if (auxf_obs) auxf_obs[pix] = (uint8_t)face;
+            }
+        }
+        if (PACKED) {
+            // four consecutive lanes hold four consecutive pixels of one row = 12 bytes = three aligned
+            // dwords, written by the first three lanes of the quad: dword m holds the upper 4-m bytes'
+            // worth of pixel m and the lower m+1 bytes of pixel m+1.
+            const uint32_t next = next_in_quad(colour);
+            const uint32_t word = (colour >> (8 * quad)) | (next << (24 - 8 * quad));
+            if (quad < 3)
+                *reinterpret_cast<uint32_t*>(rgb_obs + (3u * pix + (uint32_t)quad)) = word;
+        } else if (active) {
+            uint8_t* out = rgb_obs + 3u * pix;
+            out[0] = (uint8_t)colour;
+            out[1] = (uint8_t)(colour >> 8);
+            out[2] = (uint8_t)(colour >> 16);
+        }
+    };
+
+    // The tile loop is software-pipelined by one tile: a trip first requests the material bytes of the tile
+    // traced in the previous trip, then traces its own tile, and only then shades and stores the previous
+    // one, so that the global fetch hides behind a whole traversal.  (The request is issued in the trip that
+    // consumes it: a value still in flight across the loop's back edge would be waited for there.)
+    int pend_idx = -1, pend_face = 255;
+    float pend_t = 0.0f;
+    uint32_t pend_pix = 0;
+    bool pend_active = false, pending = false;
     for (int tile = tile_begin + wave; tile < tile_end; tile += waves) {
+        // lanes without a hit (idx -1 = 0xffffffff) read the last voxel and drop it later: no branch
+        const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
+
         const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
         const int col = tx * kTile + lx, row = ty * kTile + ly;
         // PACKED launches have W and H multiples of the tile size: every lane owns a pixel
@@ -893,42 +937,15 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
             h = trace_generic(reinterpret_cast<const uint32_t*>(lds_rows), 2 * g.rowwords_x, P, d, X, Y, Z,
                               origin_in_grid, p.max_steps);
 
-        // a6: shade
-        const bool hit = h.idx >= 0;
-        uint32_t colour = p.sky_packed;
-        float depth = 0.0f;
-        int material = 0, face = 255;
-        if (hit) {
-            material = vox_env[min((uint32_t)h.idx, last_voxel)];
-            colour = lut_lds[mad24s(h.face, p.materials_plus_one, min(material, last_material))];
-            depth = h.t;
-            face = h.face;
-        }
-
-        // a7: stores
-        const uint32_t pix = (uint32_t)mad24s(crow, p.W, ccol);
-        if (active) {
-            depth_obs[pix] = depth;
-            if (AUX) {
-                if (auxm_obs) auxm_obs[pix] = (uint8_t)material;
-                if (auxh_obs) auxh_obs[pix] = h.idx;
-                if (auxf_obs) auxf_obs[pix] = (uint8_t)face;
-            }
-        }
-        if (PACKED) {
-            // four consecutive lanes hold four consecutive pixels of one row = 12 bytes = three aligned
-            // dwords, written by the first three lanes of the quad: dword m holds the upper 4-m bytes'
-            // worth of pixel m and the lower m+1 bytes of pixel m+1.
-            const uint32_t next = next_in_quad(colour);
-            const uint32_t word = (colour >> (8 * quad)) | (next << (24 - 8 * quad));
-            if (quad < 3)
-                *reinterpret_cast<uint32_t*>(rgb_obs + (3u * pix + (uint32_t)quad)) = word;
-        } else if (active) {
-            uint8_t* out = rgb_obs + 3u * pix;
-            out[0] = (uint8_t)colour;
-            out[1] = (uint8_t)(colour >> 8);
-            out[2] = (uint8_t)(colour >> 16);
-        }
+        if (pending) shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
+        pend_idx = h.idx; pend_face = h.face; pend_t = h.t;
+        pend_pix = (uint32_t)mad24s(crow, p.W, ccol);
+        pend_active = active;
+        pending = true;
+    }
+    if (pending) {
+        const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
+        shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
     }
 }
 
