@@ -24,7 +24,7 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-class GpuRun:
+class GpuRender:
     """Owns the output tensors of one batch and renders into them."""
 
     def __init__(self, batch: binding.Batch, W, H, aux=True):
@@ -80,7 +80,7 @@ def _gpu_for(spec, voxels, palette, cams, self_voxel=None, device_src=True, aux=
     else:
         batch.upload_worlds(voxels, palette, stream=_stream())
         batch.set_cameras(np.ascontiguousarray(cams), self_voxel, stream=_stream())
-    return GpuRun(batch, spec.width, spec.height, aux=aux)
+    return GpuRender(batch, spec.width, spec.height, aux=aux)
 
 
 def _obs_sample(spec, count):
@@ -175,8 +175,8 @@ def test_config2_full_size_first_and_last_step(lib, orc):
     cams_d = torch.from_numpy(wl.cameras).cuda()            # [100, 8192, 5]
     batch = binding.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height)
     batch.upload_worlds(vox_d, pal_d, stream=_stream())
-    plain = GpuRun(batch, spec.width, spec.height, aux=False)
-    full = GpuRun(batch, spec.width, spec.height, aux=True)
+    plain = GpuRender(batch, spec.width, spec.height, aux=False)
+    full = GpuRender(batch, spec.width, spec.height, aux=True)
     ob = orc.OracleBatch(spec.num_envs, spec.agents_per_env, spec.grid, spec.width, spec.height, spec.num_materials)
     ob.upload_worlds(wl.voxels, wl.palette)
     for step in (0, spec.steps - 1):
@@ -201,7 +201,7 @@ def test_config3_dynamic_worlds_and_own_bodies(lib, orc):
     wl = synth.generate(3)
     spec = wl.spec
     batch = binding.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height)
-    run = GpuRun(batch, spec.width, spec.height, aux=True)
+    run = GpuRender(batch, spec.width, spec.height, aux=True)
     ob = orc.OracleBatch(spec.num_envs, spec.agents_per_env, spec.grid, spec.width, spec.height, spec.num_materials)
     pal_d = torch.from_numpy(wl.palette).cuda()
     vox, cams, selfv = wl.voxels, wl.cameras[0], wl.self_voxel[0]
@@ -232,7 +232,7 @@ def test_config3_sparse_edits_match_full_uploads(lib, orc):
     spec = wl.spec
     mk = lambda: binding.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height)
     full, sparse_d, sparse_h = mk(), mk(), mk()
-    runs = [GpuRun(b, spec.width, spec.height, aux=True) for b in (full, sparse_d, sparse_h)]
+    runs = [GpuRender(b, spec.width, spec.height, aux=True) for b in (full, sparse_d, sparse_h)]
     ob = orc.OracleBatch(spec.num_envs, spec.agents_per_env, spec.grid, spec.width, spec.height, spec.num_materials)
     vox, cams, selfv = wl.voxels, wl.cameras[0], wl.self_voxel[0]
     for b in (full, sparse_d, sparse_h):
@@ -316,7 +316,7 @@ def test_config4_large_grid_large_image(lib, orc):
     ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
     total = _compare_all(ob, run, "cfg4", chunk=128)
     assert total["pixels"] == spec.num_obs * spec.width * spec.height
-    plain = GpuRun(run.batch, spec.width, spec.height, aux=False)
+    plain = GpuRender(run.batch, spec.width, spec.height, aux=False)
     plain.render()
     assert torch.equal(plain.rgb, run.rgb) and torch.equal(plain.depth.view(torch.int32), run.depth.view(torch.int32))
 
@@ -449,7 +449,7 @@ def test_randomized_configurations_against_the_oracle(lib, orc):
         batch.upload_worlds(torch.from_numpy(vox).cuda(), torch.from_numpy(pal).cuda(), stream=_stream())
         batch.set_cameras(torch.from_numpy(cams).cuda(), None if selfv is None else torch.from_numpy(selfv).cuda(),
                           stream=_stream())
-        run = GpuRun(batch, W, H, aux=True)
+        run = GpuRender(batch, W, H, aux=True)
         run.render()
         g = run.numpy()
         _pixelwise_rule(g, ref, f"seed {seed} grid {grid} image {W}x{H}")
@@ -490,10 +490,10 @@ def test_randomized_entry_point_sequences(lib, orc):
         batch.set_cameras(torch.from_numpy(cams).cuda(), None if selfv is None else torch.from_numpy(selfv).cuda(),
                           stream=_stream())
         ob.set_cameras(cams, selfv)
-        full = GpuRun(batch, W, H, aux=True)
+        full = GpuRender(batch, W, H, aux=True)
         full.render()
         _pixelwise_rule(full.numpy(), ob.render(), where + " uploads")
-        plain = GpuRun(batch, W, H, aux=False)
+        plain = GpuRender(batch, W, H, aux=False)
         plain.render()
         assert torch.equal(plain.rgb, full.rgb) and torch.equal(plain.depth.view(torch.int32), full.depth.view(torch.int32)), where
         # sparse edits, each voxel at most once
@@ -571,7 +571,7 @@ def test_partial_uploads_and_palette_keep(lib, orc):
     spec = wl.spec
     ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
     batch = binding.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height)
-    run = GpuRun(batch, spec.width, spec.height)
+    run = GpuRender(batch, spec.width, spec.height)
     cams_d = torch.from_numpy(wl.cameras[0]).cuda()
     # render before anything is there
     with pytest.raises(binding.MvError) as e:
@@ -717,7 +717,7 @@ def test_step_replays_from_a_hip_graph(lib, orc):
     vox, cams, selfv = wl.voxels, wl.cameras[0], wl.self_voxel[0]
     for b in (batch, eager):
         b.upload_worlds(vox, wl.palette)
-    run_g, run_e = GpuRun(batch, spec.width, spec.height, aux=False), GpuRun(eager, spec.width, spec.height, aux=False)
+    run_g, run_e = GpuRender(batch, spec.width, spec.height, aux=False), GpuRender(eager, spec.width, spec.height, aux=False)
     max_edits = 8192
     cams_in = torch.from_numpy(cams).cuda()
     self_in = torch.from_numpy(selfv).cuda()
