@@ -206,10 +206,17 @@ const char* mv_last_error(void);
  *                        is voxel (i,j,k); *top_layer points to one int32: 1 + the highest layer k
  *                        that holds a solid voxel (0 for an empty grid).
  *   mv_debug_camera_records : device pointer to the [N*A] 64-byte camera records
- *                        (float P[3], F[3], R[3], U[3]; int32 self_lo, self_hi; 8 bytes pad). */
+ *                        (float P[3], F[3], R[3], U[3]; int32 self_lo, self_hi; 8 bytes pad).
+ *   mv_debug_set_staged_layers : the render kernel keeps only the lowest layers of a grid on chip, as many
+ *                        as the tallest world uploaded so far needs (it learns that number from its own
+ *                        kernels, without synchronising); an environment that needs more is traced
+ *                        through device memory instead, with identical results.  This call fixes the number
+ *                        (1..Z) so that tests can reach that path; 0 returns to the automatic choice.
+ *                        Errors: MV_ERR_ARG, MV_ERR_RANGE. */
 int mv_debug_occupancy(mv_batch* batch, int32_t env, const uint64_t** x_rows, int32_t* x_row_words,
                        const uint64_t** y_rows, int32_t* y_row_words, const int32_t** top_layer);
 int mv_debug_camera_records(mv_batch* batch, const void** records);
+int mv_debug_set_staged_layers(mv_batch* batch, int32_t layers);
 
 #ifdef __cplusplus
 }

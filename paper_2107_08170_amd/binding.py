@@ -19,7 +19,8 @@ FACE_INSIDE, FACE_MISS = 6, 255
 
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
            "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_host_alloc", "mv_host_free",
-           "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records")
+           "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records",
+           "mv_debug_set_staged_layers")
 
 
 class MvConfig(C.Structure):
@@ -76,6 +77,7 @@ def load_library():
     lib.mv_debug_occupancy.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_int32), C.POINTER(vp),
                                        C.POINTER(C.c_int32), C.POINTER(vp)]
     lib.mv_debug_camera_records.argtypes = [vp, C.POINTER(vp)]
+    lib.mv_debug_set_staged_layers.argtypes = [vp, C.c_int32]
     _lib = lib
     return lib
 
@@ -217,6 +219,9 @@ class Batch:
         _check(load_library().mv_debug_occupancy(self._h, env, C.byref(xp), C.byref(xw), C.byref(yp), C.byref(yw),
                                                  C.byref(tp)))
         return xp.value, xw.value, yp.value, yw.value, tp.value
+
+    def debug_set_staged_layers(self, layers: int) -> None:
+        _check(load_library().mv_debug_set_staged_layers(self._h, layers))
 
     def debug_camera_records(self) -> int:
         ptr = C.c_void_p()

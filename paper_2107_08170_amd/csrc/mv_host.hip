@@ -79,6 +79,12 @@ struct mv_batch {
     float* d_cams = nullptr;          // staging for host-supplied cameras
     int32_t* d_self = nullptr;
     mv::CameraRecord* d_rec = nullptr;
+    // tallest world so far: exact on the device, and a pinned host word that kernels keep up to date and
+    // that mv_render_batch reads without synchronising to choose how many layers to stage
+    int32_t* d_height = nullptr;
+    int32_t* h_height = nullptr;          // pinned host memory
+    int32_t* h_height_dev = nullptr;      // the same word as the device addresses it
+    int forced_layers = 0;                // debug override (0 = automatic)
 
     std::vector<uint8_t> env_has_grid, env_has_palette;
     int envs_with_grid = 0, envs_with_palette = 0;
@@ -91,6 +97,8 @@ static void free_batch(mv_batch* b)
     (void)hipFree(b->d_vox); (void)hipFree(b->d_bits); (void)hipFree(b->d_ztop); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
     (void)hipFree(b->d_sx); (void)hipFree(b->d_sy); (void)hipFree(b->d_cams); (void)hipFree(b->d_self);
     (void)hipFree(b->d_rec); (void)hipFree(b->d_edits); (void)hipFree(b->d_active); (void)hipFree(b->d_fraction);
+    (void)hipFree(b->d_height);
+    if (b->h_height) (void)hipHostFree(b->h_height);
     delete b;
 }
 
@@ -138,7 +146,7 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     const long long num_obs = (long long)cfg->num_envs * cfg->agents_per_env;
     if (num_obs > (1ll << 24)) return fail(MV_ERR_ARG, "mv_create_batch: more than 2^24 observations");
     const mv::GridLayout layout = mv::make_layout(cfg->grid_x, cfg->grid_y, cfg->grid_z);
-    const mv::LdsPlan plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1);
+    const mv::LdsPlan plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1, cfg->grid_z);
     if (plan.bytes == 0)
         return fail(MV_ERR_CAPACITY, "mv_create_batch: the occupancy bit rows of one %dx%dx%d grid do not fit in %zu bytes of LDS",
                     cfg->grid_x, cfg->grid_y, cfg->grid_z, mv::kLdsBudget);
@@ -188,6 +196,13 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     alloc((void**)&b->d_rec, (size_t)num_obs * sizeof(mv::CameraRecord));
     alloc((void**)&b->d_active, N);
     alloc((void**)&b->d_fraction, (size_t)num_obs * 4);
+    alloc((void**)&b->d_height, 4);
+    if (e == hipSuccess) e = hipMemset(b->d_height, 0, 4);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&b->h_height, 4, hipHostMallocMapped);
+    if (e == hipSuccess) {
+        *b->h_height = 0;
+        e = hipHostGetDevicePointer((void**)&b->h_height_dev, b->h_height, 0);
+    }
     if (e == hipSuccess) e = mv::launch_pixel_scalars(b->d_sx, b->d_sy, cfg->width, cfg->height, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
     if (e == hipSuccess) e = mv::prepare_render(plan.bytes);
@@ -230,11 +245,13 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
         // pageable host memory: make sure the runtime is done reading it before we return
         MV_HIP(hipStreamSynchronize(stream));
         MV_HIP(mv::launch_pack(vox_dst, vox_dst, bits_dst, ztop_dst, count, b->layout, palette ? pal_dst : nullptr,
-                               pal_dst, lut_dst, b->materials_plus_one, b->intensity, stream));
+                               pal_dst, lut_dst, b->materials_plus_one, b->intensity,
+                               mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
     } else {
         // one launch: material copy, bit rows, palette copy and colour tables
         MV_HIP(mv::launch_pack(voxels, vox_dst, bits_dst, ztop_dst, count, b->layout, palette, pal_dst, lut_dst,
-                               b->materials_plus_one, b->intensity, stream));
+                               b->materials_plus_one, b->intensity,
+                               mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
     }
 
     for (int e = first_env; e < first_env + count; ++e) {
@@ -290,7 +307,8 @@ int mv_update_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32
         d_env = s_env; d_idx = s_idx; d_mat = s_mat;
     }
     MV_HIP(mv::launch_update_voxels(d_env, d_idx, d_mat, count, b->d_vox, b->d_bits, b->d_ztop, b->cfg.num_envs,
-                                    b->voxels_per_env, b->cfg.num_materials, b->layout, stream));
+                                    b->voxels_per_env, b->cfg.num_materials, b->layout,
+                                    mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
     return MV_OK;
 }
 
@@ -335,13 +353,27 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     DeviceScope scope(b->cfg.device);
     if (!scope.ok()) return fail(MV_ERR_HIP, "mv_render_batch: cannot select device %d", b->cfg.device);
 
+    // How many layers of a row-scan grid to stage: as many as the tallest world the kernels have reported
+    // so far (read without synchronising: a value that is out of date costs speed, never correctness -- a
+    // workgroup whose world is taller than what was staged traces through global memory and reports it),
+    // all of them before the first report.
+    int staged = b->cfg.grid_z;
+    if (b->layout.fast) {
+        // one layer above the tallest world: cameras that fly above their world stand in that (empty) layer
+        const int seen = b->forced_layers > 0 ? b->forced_layers : *(volatile int32_t*)b->h_height + 1;
+        if (seen > 1 && seen < staged) staged = seen;
+    }
+    const mv::LdsPlan plan = mv::plan_lds(b->layout, b->cfg.width, b->cfg.height, b->materials_plus_one, staged);
+
     mv::RenderParams p{};
+    p.staged_layers = staged;
+    p.heights = mv::HeightFeedback{ b->d_height, b->h_height_dev };
     p.active = b->all_active ? nullptr : b->d_active;
     p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
     p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
     p.g = b->layout;
     p.voxels_per_env = b->voxels_per_env;
-    p.threads = b->plan.threads;
+    p.threads = plan.threads;
     p.W = b->cfg.width; p.H = b->cfg.height; p.A = b->cfg.agents_per_env;
     p.materials_plus_one = b->materials_plus_one;
     p.tiles_x = (p.W + mv::kTile - 1) / mv::kTile;
@@ -352,17 +384,15 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
         // Strips of an observation per workgroup.  Two pulls: (1) enough workgroups to fill 256 CUs a few
         // times over (about 6144: on 1024 observations of 40x40x16 worlds, 6 strips per observation render
         // 6 % faster than 8 and 23 % faster than whole observations); (2) when a CU holds four or more
-        // workgroups, so that one workgroup's staging hides behind the others' tracing, about 12 tiles per
-        // wave balance the tail best (3 strips of 48 tiles: 5 % faster than 2 on the dynamic workload,
-        // neutral on the benchmark workload).  Grids that leave room for only two workgroups per CU render
-        // whole observations: every strip would re-stage 67 KB with nothing to hide it (-9 % when split).
+        // workgroups, so that one workgroup's staging hides behind the others' tracing, three strips per
+        // observation balance the tail best (40x40x16, 128x72: 3 strips of 48 tiles 5 % faster than 2 on
+        // the dynamic workload; 64x64x32 terrain, 256x144, 16 staged layers: 3 strips of 192 tiles 6 %
+        // faster than whole observations or 6 strips).  Grids that leave room for only two workgroups per
+        // CU render whole observations: every strip would re-stage the rows with nothing to hide it.
         const int waves = p.threads / 64;
         const long long target_blocks = 256ll * 24;
         long long strips = (target_blocks + b->num_obs - 1) / b->num_obs;
-        if (mv::kLdsBudget / b->plan.bytes >= 4) {
-            const long long balanced = (p.tiles_per_obs + 12 * waves - 1) / (12 * waves);
-            if (balanced > strips) strips = balanced;
-        }
+        if (mv::kLdsBudget / plan.bytes >= 4 && strips < 3) strips = 3;
         if (strips < 1) strips = 1;
         tpb = (int)((p.tiles_per_obs + strips - 1) / strips);
         const int min_tpb = waves * 2;
@@ -377,7 +407,7 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.blocks_per_xcd = (uint32_t)((total + mv::kXcds - 1) / mv::kXcds);
     p.sky_packed = (uint32_t)b->cfg.sky_rgb[0] | ((uint32_t)b->cfg.sky_rgb[1] << 8) | ((uint32_t)b->cfg.sky_rgb[2] << 16);
     p.max_steps = p.g.X + p.g.Y + p.g.Z + 3;
-    MV_HIP(mv::launch_render(p, b->plan.bytes, (hipStream_t)hip_stream));
+    MV_HIP(mv::launch_render(p, plan.bytes, (hipStream_t)hip_stream));
     return MV_OK;
 }
 
@@ -480,6 +510,15 @@ int mv_debug_occupancy(mv_batch* b, int32_t env, const uint64_t** x_rows, int32_
     *y_rows = *x_rows + b->layout.xrow_words;
     *y_row_words = b->layout.rowwords_y;
     *top_layer = b->d_ztop + env;
+    return MV_OK;
+}
+
+int mv_debug_set_staged_layers(mv_batch* b, int32_t layers)
+{
+    if (!b) return fail(MV_ERR_ARG, "mv_debug_set_staged_layers: null batch");
+    if (layers < 0 || layers > b->cfg.grid_z)
+        return fail(MV_ERR_RANGE, "mv_debug_set_staged_layers: %d outside 0..%d", layers, b->cfg.grid_z);
+    b->forced_layers = layers;
     return MV_OK;
 }
 

@@ -34,6 +34,16 @@ struct GridLayout {
     int32_t fast;                         // 1: X,Y <= 64 (one word per row) -> row-scan traversal
 };
 
+// The tallest world a batch has held so far (1 + highest solid layer over all environments, never
+// lowered): `device_max` is exact; `host_max` is a word of pinned host memory that kernels update when the
+// device word rises and that the host reads WITHOUT synchronising to decide how many layers the next
+// render stages in LDS.  A stale value costs speed only: workgroups that need more layers than were staged
+// trace through the rows in global memory instead, and report what they needed.
+struct HeightFeedback {
+    int32_t* device_max;
+    int32_t* host_max;      // device-visible address of the pinned host word
+};
+
 struct RenderParams {
     const uint64_t*     bits;             // [N][env_words]
     const int32_t*      ztop;             // [N] 1 + highest solid layer (0 = empty world)
@@ -57,6 +67,8 @@ struct RenderParams {
     uint32_t sky_packed;
     int32_t max_steps;
     int32_t threads;                      // workgroup size (multiple of 64)
+    int32_t staged_layers;                // row-scan grids: layers 0 .. staged_layers-1 of the bit rows go to LDS
+    HeightFeedback heights;
 };
 
 GridLayout make_layout(int X, int Y, int Z);
@@ -66,17 +78,20 @@ struct LdsPlan {
     size_t bytes;         // dynamic LDS per workgroup
     int    threads;       // workgroup size that keeps a CU busy with that much LDS
 };
-LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one);
+// staged_layers: how many z layers of a row-scan grid the workgroup keeps in LDS (1..Z; ignored for other grids)
+LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers);
 
 // Launchers (mv_kernels.hip).  All enqueue on `stream` and return hipGetLastError().
 hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t stream);
 // pal_src == nullptr keeps the palettes; otherwise [count][M+1][3] device bytes (may equal pal_dst)
 hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
                        const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
-                       int materials_plus_one, const float intensity[kNumFaces], hipStream_t stream);
+                       int materials_plus_one, const float intensity[kNumFaces], const HeightFeedback& heights,
+                       hipStream_t stream);
 hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, const uint8_t* material, int count,
                                 uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
-                                int num_materials, const GridLayout& g, hipStream_t stream);
+                                int num_materials, const GridLayout& g, const HeightFeedback& heights,
+                                hipStream_t stream);
 hipError_t launch_cameras(const float* cams, const int32_t* self_voxel, CameraRecord* rec, int num_obs,
                           double tan_half_x, double tan_half_y, int plane_voxels, hipStream_t stream);
 struct BarParams {

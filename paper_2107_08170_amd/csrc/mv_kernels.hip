@@ -37,13 +37,14 @@ static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
 // LDS map (bytes):  [4 scan-class records, 80 B each] | [sx: W floats][sy: H floats] |
 //                   [colour table 7*(M+1) dwords] | bit rows
-// fast grids stage four row arrays (x, x mirrored, y, y mirrored); others stage the x rows only.
+// fast grids stage four row arrays (x, x mirrored, y, y mirrored) of `staged_layers` layers each; others stage
+// all x rows.
 struct LdsMap {
     uint32_t scalars, classes, lut, rows;
     uint32_t total;
 };
 
-static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one)
+static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers)
 {
     LdsMap m{};
     size_t off = 0;
@@ -52,17 +53,15 @@ static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one)
     m.lut = (uint32_t)off;
     off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
     m.rows = (uint32_t)off;
-    off += g.fast ? 2 * (size_t)g.env_words * 8 : (size_t)g.xrow_words * 8;
+    off += g.fast ? 16 * (size_t)staged_layers * (size_t)(g.X + g.Y) : (size_t)g.xrow_words * 8;
     m.total = (uint32_t)off;
     return m;
 }
 
-LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one)
+LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers)
 {
     LdsPlan plan{};
-    size_t rows = g.fast ? 2 * (size_t)g.env_words * 8 : (size_t)g.xrow_words * 8;
-    (void)rows;
-    const LdsMap m = lds_map(g, W, H, materials_plus_one);
+    const LdsMap m = lds_map(g, W, H, materials_plus_one, staged_layers);
     if (m.total > kLdsBudget) return plan;                                  // bytes == 0: does not fit
     plan.bytes = m.total;
     // as many waves per workgroup as fill the CU's wave slots with the workgroups its LDS can hold
@@ -180,6 +179,18 @@ __device__ __forceinline__ uint64_t transpose_bits_across_lanes(uint64_t row, in
     return ((uint64_t)hi << 32) | lo;
 }
 
+// Called by one thread for a world (or a voxel) whose top is `top`: raises the batch's device word and, when
+// it rose, the pinned host word (a system-scope atomic maximum, so that two risers cannot leave the smaller
+// value behind).
+__device__ __forceinline__ void report_height(const HeightFeedback& fb, int top)
+{
+    if (!fb.device_max) return;
+    // thousands of worlds report per upload and almost none of them raises the word: look before the atomic
+    if (top <= __hip_atomic_load(fb.device_max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+    const int old = atomicMax(fb.device_max, top);
+    if (top > old) __hip_atomic_fetch_max(fb.host_max, top, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // kPackPrefetch = dwords of the next layer each lane keeps in flight: 8 covers layers up to 2 KiB (40x40), 16
 // layers up to 4 KiB (64x64); the deeper variant costs registers, so small layers keep the shallow one.
 template <int kPackPrefetch>
@@ -187,7 +198,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
                                                             uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
                                                             GridLayout g, int vec_ok, const uint8_t* __restrict__ pal_src,
                                                             uint8_t* __restrict__ pal_dst, uint32_t* __restrict__ lut_dst,
-                                                            int materials_plus_one, Intensities I)
+                                                            int materials_plus_one, Intensities I, HeightFeedback heights)
 {
     extern __shared__ __align__(16) uint8_t layer_lds[];   // one layer per wave, padded to 16 bytes
     if (pal_src) {
@@ -310,12 +321,16 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     }
     if (lane == 0) atomicMax(&top_lds, top);
     __syncthreads();
-    if (threadIdx.x == 0) ztop_dst[env] = top_lds;
+    if (threadIdx.x == 0) {
+        ztop_dst[env] = top_lds;
+        report_height(heights, top_lds);
+    }
 }
 
 hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
                        const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
-                       int materials_plus_one, const float intensity[kNumFaces], hipStream_t stream)
+                       int materials_plus_one, const float intensity[kNumFaces], const HeightFeedback& heights,
+                       hipStream_t stream)
 {
     Intensities I;
     for (int f = 0; f < kNumFaces; ++f) I.v[f] = intensity[f];
@@ -326,10 +341,10 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
                        ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
     if (XY / 4 <= 8 * 64)
         hipLaunchKernelGGL(pack_kernel<8>, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
-                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
+                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I, heights);
     else
         hipLaunchKernelGGL(pack_kernel<16>, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
-                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I);
+                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I, heights);
     return hipGetLastError();
 }
 
@@ -341,7 +356,7 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
 __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int32_t* __restrict__ voxel_index,
                                      const uint8_t* __restrict__ material, int count, uint8_t* __restrict__ vox,
                                      uint64_t* __restrict__ bits, int32_t* __restrict__ ztop, int num_envs,
-                                     int voxels_per_env, int num_materials, GridLayout g)
+                                     int voxels_per_env, int num_materials, GridLayout g, HeightFeedback heights)
 {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= count) return;
@@ -358,7 +373,7 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
     if (m != 0) {
         atomicOr(xrow, 1ull << (i & 63));
         atomicOr(yrow, 1ull << (j & 63));
-        atomicMax(ztop + n, k + 1);
+        if (atomicMax(ztop + n, k + 1) < k + 1) report_height(heights, k + 1);
     } else {
         atomicAnd(xrow, ~(1ull << (i & 63)));
         atomicAnd(yrow, ~(1ull << (j & 63)));
@@ -367,10 +382,10 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
 
 hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, const uint8_t* material, int count,
                                 uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
-                                int num_materials, const GridLayout& g, hipStream_t stream)
+                                int num_materials, const GridLayout& g, const HeightFeedback& heights, hipStream_t stream)
 {
     hipLaunchKernelGGL(update_voxels_kernel, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
-                       material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g);
+                       material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g, heights);
     return hipGetLastError();
 }
 
@@ -451,11 +466,14 @@ struct alignas(16) ScanClass {
 };
 static_assert(sizeof(ScanClass) == 80, "scan class record must be 80 bytes");
 
-// Plain 3D-DDA through the x rows (any row width).  Used for cameras outside the grid and for grids
-// wider than 64 voxels.  Crossing parameters are t = n*|1/d| + t_first (one fused op, error relative
+// Plain 3D-DDA through the x rows (any row width), in LDS or in global memory.  Used for grids wider than 64
+// voxels, for cameras outside the grid, and for workgroups whose world is taller than the layers staged.  Crossing parameters are t = n*|1/d| + t_first (one fused op, error relative
 // to t itself) rather than accumulated.
+// self_lo / self_hi: voxels this camera must not see (-1 = none); callers that have already removed the body
+// from their copy of the rows pass -1.
 __device__ __forceinline__ Hit trace_generic(const uint32_t* __restrict__ xrows32, int rowdwords, const float P[3],
-                                             const float d[3], int X, int Y, int Z, bool origin_in_grid, int max_steps)
+                                             const float d[3], int X, int Y, int Z, bool origin_in_grid, int max_steps,
+                                             int self_lo, int self_hi)
 {
     const float kInf = __builtin_inff();
     const int dim[3] = { X, Y, Z };
@@ -507,7 +525,8 @@ __device__ __forceinline__ Hit trace_generic(const uint32_t* __restrict__ xrows3
         t_exit = fminf(t_exit, te);
     }
     auto solid = [&](int i, int j, int k) -> bool {
-        return (xrows32[(k * Y + j) * rowdwords + (i >> 5)] >> (i & 31)) & 1u;
+        const int idx = (k * Y + j) * X + i;
+        return ((xrows32[(k * Y + j) * rowdwords + (i >> 5)] >> (i & 31)) & 1u) && idx != self_lo && idx != self_hi;
     };
     int face = entry_axis >= 0 ? 2 * entry_axis + (pos[entry_axis] ? 0 : 1) : 6;
     if (solid(cell[0], cell[1], cell[2])) return Hit{ (cell[2] * Y + cell[1]) * X + cell[0], face, t0 };
@@ -598,7 +617,7 @@ __device__ __forceinline__ int mad24s(int a, int b_uniform, int c)
 // every input: each turn advances n_v or n_z, the crossing parameters |n|*dt + t0 never decrease, and
 // t_end is that same expression at the last plane of each axis, so t_out reaches t_end after at most
 // V + Z + 2 turns; a NaN anywhere makes the comparison false and ends it at once.
-// n_v and n_z count crossings with the sign of the direction, so that the cell is (v0 + n_v, k0 + n_z).
+// n_v and n_z count crossings with the sign of the direction, so that the cell is (v0 + n_v, kc + n_z).
 __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz, float hi_z, float lo_z,
                                           float nz_pos, float nz_neg, int XY)
 {
@@ -703,7 +722,7 @@ __device__ __forceinline__ uint32_t next_in_quad(uint32_t v)
 }
 
 template <bool AUX, bool PACKED, bool FAST>
-__global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void render_kernel(RenderParams p)
 {
     extern __shared__ __align__(16) uint8_t lds[];
     const int threads = p.threads;
@@ -739,6 +758,28 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
     const float Ux = recp->U[0], Uy = recp->U[1], Uz = recp->U[2];
     const int self_lo = recp->self_lo, self_hi = recp->self_hi;
 
+    const bool origin_in_grid = P[0] >= 0.0f && P[0] <= (float)X && P[1] >= 0.0f && P[1] <= (float)Y &&
+                                P[2] >= 0.0f && P[2] <= (float)Z;
+    const int k0 = min(max((int)floorf(P[2]), 0), Z - 1);
+    // Layers the rays of this camera can reach.  Above the highest solid layer of the environment a rising
+    // ray can only miss, so the grid is cut there.  A camera that is itself above every solid sits, for the
+    // row scan, in one tall empty layer that reaches from the top of the solids upwards: its layer index is
+    // kc = ztop, the plane below it is z = ztop (however far down that is), and only layers 0 .. ztop are
+    // ever read (layer ztop is empty by definition).
+    const int ztop = p.ztop[env];
+    const int kc = min(k0, ztop);
+    const int zlim = kc + 1 > ztop ? kc + 1 : ztop;
+    // Row scan: only if those layers were staged.  The launch stages as many layers as the tallest world
+    // the host has heard of; a taller one is traced through the rows in global memory, cell by cell, and
+    // says so, so that the next launch stages enough.
+    const int staged = FAST ? p.staged_layers : Z;
+    const bool use_rows = FAST && origin_in_grid && zlim <= staged;
+    const int sxw = staged * Y, syw = staged * X;          // words of one staged x / y row array
+    if (FAST && origin_in_grid && !use_rows && threadIdx.x == 0 && p.heights.device_max) {
+        atomicMax(p.heights.device_max, ztop);
+        __hip_atomic_fetch_max(p.heights.host_max, ztop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+
     {   // a3: stage pixel scalars, colour table and this environment's bit rows
         for (int i = threadIdx.x; i < p.W; i += threads) lds_sx[i] = p.sx[i];
         for (int i = threadIdx.x; i < p.H; i += threads) lds_sy[i] = p.sy[i];
@@ -747,30 +788,28 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         for (int i = threadIdx.x; i < kNumFaces * p.materials_plus_one; i += threads) ll[i] = gl[i];
         const uint64_t* gb = p.bits + (size_t)env * g.env_words;
         if (FAST) {
-            // arrays: [x rows][x rows mirrored][y rows][y rows mirrored]
-            uint64_t* ax = lds_rows;
-            uint64_t* axm = ax + g.xrow_words;
-            uint64_t* ay = axm + g.xrow_words;
-            uint64_t* aym = ay + g.yrow_words;
-            for (int w = threadIdx.x; w < g.xrow_words; w += threads) {
-                uint64_t v = gb[w];
-                ax[w] = v;
-                axm[w] = __brevll(v) >> (64 - X);
-            }
-            for (int w = threadIdx.x; w < g.yrow_words; w += threads) {
-                uint64_t v = gb[g.xrow_words + w];
-                ay[w] = v;
-                aym[w] = __brevll(v) >> (64 - Y);
+            if (use_rows) {
+                // arrays: [x rows][x rows mirrored][y rows][y rows mirrored], layers 0 .. staged-1 of each
+                uint64_t* ax = lds_rows;
+                uint64_t* axm = ax + sxw;
+                uint64_t* ay = axm + sxw;
+                uint64_t* aym = ay + syw;
+                for (int w = threadIdx.x; w < sxw; w += threads) {
+                    uint64_t v = gb[w];
+                    ax[w] = v;
+                    axm[w] = __brevll(v) >> (64 - X);
+                }
+                for (int w = threadIdx.x; w < syw; w += threads) {
+                    uint64_t v = gb[g.xrow_words + w];
+                    ay[w] = v;
+                    aym[w] = __brevll(v) >> (64 - Y);
+                }
             }
         } else {
             for (int w = threadIdx.x; w < g.xrow_words; w += threads) lds_rows[w] = gb[w];
         }
     }
     __syncthreads();
-
-    const bool origin_in_grid = P[0] >= 0.0f && P[0] <= (float)X && P[1] >= 0.0f && P[1] <= (float)Y &&
-                                P[2] >= 0.0f && P[2] <= (float)Z;
-    const int k0 = min(max((int)floorf(P[2]), 0), Z - 1);
 
     // This workgroup's copy of the rows is private to one camera: remove the camera's own body from it
     // once, instead of testing for it at every step.
@@ -779,20 +818,22 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         if (s >= 0 && s < X * Y * Z) {
             int k = s / (X * Y), rem = s - k * X * Y, j = rem / X, i = rem - j * X;
             if (FAST) {
-                uint64_t* ax = lds_rows;
-                uint64_t* axm = ax + g.xrow_words;
-                uint64_t* ay = axm + g.xrow_words;
-                uint64_t* aym = ay + g.yrow_words;
-                ax[k * Y + j] &= ~(1ull << i);
-                axm[k * Y + j] &= ~(1ull << (X - 1 - i));
-                ay[k * X + i] &= ~(1ull << j);
-                aym[k * X + i] &= ~(1ull << (Y - 1 - j));
+                if (use_rows && k < staged) {
+                    uint64_t* ax = lds_rows;
+                    uint64_t* axm = ax + sxw;
+                    uint64_t* ay = axm + sxw;
+                    uint64_t* aym = ay + syw;
+                    ax[k * Y + j] &= ~(1ull << i);
+                    axm[k * Y + j] &= ~(1ull << (X - 1 - i));
+                    ay[k * X + i] &= ~(1ull << j);
+                    aym[k * X + i] &= ~(1ull << (Y - 1 - j));
+                }
             } else {
                 lds_rows[(k * Y + j) * g.rowwords_x + (i >> 6)] &= ~(1ull << (i & 63));
             }
         }
     }
-    if (FAST && threadIdx.x >= 64 && threadIdx.x < 68) {
+    if (use_rows && threadIdx.x >= 64 && threadIdx.x < 68) {
         const int q = threadIdx.x - 64;
         const bool xmaj = q < 2, neg = q & 1;
         const int U = xmaj ? X : Y, V = xmaj ? Y : X;
@@ -817,9 +858,8 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         c.lo_v = (float)j0 - pv;
         c.nv_pos = (float)(V - 1 - j0);
         c.nv_neg = (float)j0;
-        const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? g.xrow_words : 0)
-                                                                   : 2 * g.xrow_words + (neg ? g.yrow_words : 0));
-        c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(k0 * V + j0));
+        const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? sxw : 0) : 2 * sxw + (neg ? syw : 0));
+        c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(kc * V + j0));
         c.zstride = 8 * V;
         c.um1 = U - 1;
         c.face_u = 2 * (xmaj ? 0 : 1) + (neg ? 1 : 0);
@@ -827,26 +867,25 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
         const int su = xmaj ? 1 : X;                       // voxel-index step per original u cell
         c.stride_u = neg ? -su : su;
         c.stride_v = xmaj ? X : 1;
-        c.idx0 = k0 * X * Y + j0 * c.stride_v + (neg ? (U - 1) * su : 0);
+        c.idx0 = kc * X * Y + j0 * c.stride_v + (neg ? (U - 1) * su : 0);
         c.zstride_neg = -8 * V;
         *reinterpret_cast<ScanClass*>(lds + off_classes + q * 80) = c;
     }
     __syncthreads();
 
-    // z constants are the same for every ray of the camera.  Above the highest solid layer of the
-    // environment a rising ray can only miss, so the grid is cut there.
-    const int ztop = p.ztop[env];
-    const int zlim = ztop > k0 ? ztop : Z;
-    const float hi_z = (float)(k0 + 1) - P[2], lo_z = (float)k0 - P[2];
-    const float nz_pos = (float)(zlim - 1 - k0), nz_neg = (float)k0;
+    // z constants are the same for every ray of the camera
+    // (hi_z: a rising ray of a camera above the solids leaves the cut grid at its first z plane: any positive
+    // distance will do, the top of its real cell is one)
+    const float hi_z = (float)(k0 + 1) - P[2], lo_z = (float)kc - P[2];
+    const float nz_pos = (float)(zlim - 1 - kc), nz_neg = (float)kc;
 
     // A camera inside a solid voxel (its own body is already gone) sees that voxel everywhere, at depth 0
     // with the "inside" face: one test per workgroup instead of one per ray.
     int cam_idx = -1;
-    if (FAST && origin_in_grid) {
+    if (use_rows) {
         const int ic = min(max((int)floorf(P[0]), 0), X - 1), jc = min(max((int)floorf(P[1]), 0), Y - 1);
-        const uint32_t bit = (uint32_t)(lds_rows[k0 * Y + jc] >> ic) & 1u;
-        if (__builtin_amdgcn_readfirstlane((int)bit)) cam_idx = (k0 * Y + jc) * X + ic;
+        const uint32_t bit = (uint32_t)(lds_rows[kc * Y + jc] >> ic) & 1u;
+        if (__builtin_amdgcn_readfirstlane((int)bit)) cam_idx = (kc * Y + jc) * X + ic;
     }
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -927,15 +966,21 @@ __global__ __launch_bounds__(1024) void render_kernel(RenderParams p)
 
         // a5: traversal
         Hit h;
-        if (FAST && origin_in_grid) {
+        if (use_rows) {
             if (cam_idx >= 0) {
                 h.idx = cam_idx; h.face = 6; h.t = 0.0f;
             } else {
                 h = trace_rows(lds_base + off_classes, d[0], d[1], d[2], hi_z, lo_z, nz_pos, nz_neg, X * Y);
             }
-        } else
+        } else if (FAST) {
+            // cameras outside the grid, and worlds taller than the staged layers: the x rows in global memory,
+            // own body skipped by index
+            h = trace_generic(reinterpret_cast<const uint32_t*>(p.bits + (size_t)env * g.env_words), 2 * g.rowwords_x, P, d,
+                              X, Y, Z, origin_in_grid, p.max_steps, self_lo, self_hi);
+        } else {
             h = trace_generic(reinterpret_cast<const uint32_t*>(lds_rows), 2 * g.rowwords_x, P, d, X, Y, Z,
-                              origin_in_grid, p.max_steps);
+                              origin_in_grid, p.max_steps, -1, -1);
+        }
 
         if (pending) shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
         pend_idx = h.idx; pend_face = h.face; pend_t = h.t;

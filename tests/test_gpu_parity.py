@@ -535,6 +535,64 @@ def test_randomized_entry_point_sequences(lib, orc):
         ob.close()
 
 
+def test_worlds_taller_than_the_staged_layers(lib, orc):
+    """The render keeps only the lowest layers of a grid on chip (as many as the tallest world it has heard of
+    needs).  With that number forced below what the worlds need, every workgroup traces through device
+    memory instead: same parity rule, own bodies still invisible.  Back on the automatic choice, the second
+    render after a synchronisation (which has learnt the height from the upload) equals the first bit for bit."""
+    wl = synth.generate(3, num_envs=12)
+    spec = wl.spec
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0], wl.self_voxel[0])
+    ref = ob.render(threads=8)
+    run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0], wl.self_voxel[0])
+    run.render()                                   # before any feedback: all layers staged
+    first = run.numpy()
+    parity.compare(first, ref, label="all layers staged")
+    torch.cuda.synchronize()
+    run.render()                                   # now with as many layers as the worlds need
+    second = run.numpy()
+    for name in ("rgb", "depth", "material", "hit_index", "face"):
+        np.testing.assert_array_equal(getattr(second, name).view(np.uint8), getattr(first, name).view(np.uint8))
+    for layers in (1, 2, 5):
+        run.batch.debug_set_staged_layers(layers)
+        run.render()
+        parity.compare(run.numpy(), ref, label=f"{layers} layers staged")
+    run.batch.debug_set_staged_layers(spec.grid[2])
+    run.render()
+    forced_all = run.numpy()
+    for name in ("rgb", "depth", "material", "hit_index", "face"):
+        np.testing.assert_array_equal(getattr(forced_all, name).view(np.uint8), getattr(first, name).view(np.uint8))
+    with pytest.raises(binding.MvError):
+        run.batch.debug_set_staged_layers(spec.grid[2] + 1)
+    run.batch.debug_set_staged_layers(0)
+
+
+def test_cameras_above_every_solid(lib, orc):
+    """Cameras that fly above their world (the row scan treats everything from the top of the solids upwards
+    as one tall empty layer), looking down, level and up, over worlds of different heights in one batch."""
+    grid = (24, 20, 12)
+    rng = np.random.default_rng(5)
+    N, A, M = 6, 4, 7
+    spec = _mini_spec(N, A, grid, 64, 40, M)
+    vox, pal = synth.random_world(rng, N, grid, 0.25, M)
+    for n in range(N):
+        vox[n, 2 + n:] = 0                          # world n is 2 + n layers tall
+    vox[N - 1] = 0                                  # and one empty world
+    cams = synth.random_cameras(rng, N * A, grid, margin=0.0, max_pitch=1.4)
+    for o in range(N * A):
+        n = o // A
+        cams[o, 2] = rng.uniform(2 + n, grid[2]) if o % A else float(2 + n)     # above the top; agent 0 exactly on it
+    cams = cams.astype(np.float32)
+    ob = _oracle_for(orc, spec, vox, pal, cams)
+    ref = ob.render()
+    run = _gpu_for(spec, vox, pal, cams)
+    for _ in range(2):                              # all layers staged, then as many as the tallest world needs
+        run.render()
+        _pixelwise_rule(run.numpy(), ref, "flying cameras")
+        torch.cuda.synchronize()
+    assert (ref.hit_index >= 0).mean() > 0.2
+
+
 def test_axis_parallel_and_vertical_rays(lib, orc):
     grid = (6, 6, 6)
     vox = np.zeros((1, 6, 6, 6), np.uint8)
