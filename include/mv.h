@@ -142,7 +142,10 @@ int mv_set_cameras(mv_batch* batch, const float* cams, const int32_t* self_voxel
  *   aux_material  : [N*A, H, W] uint8 material id of the hit voxel (0 on a miss), or NULL.
  *   aux_hit_index : [N*A, H, W] int32 linear index of the hit voxel (-1 on a miss), or NULL.
  *   aux_face      : [N*A, H, W] uint8 MV_FACE_* code, or NULL.
- * One kernel launch on `stream`; returns without synchronising.
+ * One kernel launch on `stream`; returns without synchronising.  The kernel keeps the lowest layers of each
+ * grid on chip, as many as the tallest world uploaded so far needs (learnt from earlier kernels without
+ * synchronising); the first launch after taller worlds arrive renders them through device memory (slower,
+ * same accuracy, not necessarily the same bits at exact ties), later launches adapt.
  * Errors: MV_ERR_ARG, MV_ERR_STATE (some environment or the cameras never supplied), MV_ERR_HIP. */
 int mv_render_batch(mv_batch* batch, uint8_t* rgb, float* depth, uint8_t* aux_material,
                     int32_t* aux_hit_index, uint8_t* aux_face, void* hip_stream);
