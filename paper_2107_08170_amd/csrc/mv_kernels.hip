@@ -100,6 +100,8 @@ hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t 
 // are the 64x64 bit transpose of the x rows, done across lanes without memory.  Other grids: lane r
 // gathers row r cell by cell.  Rows leave as one coalesced store per 64 rows.
 // ------------------------------------------------------------------------------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kPackThreads = 256;
 
 // Colour table entry (a6): round-to-nearest(palette value * face intensity) per channel as two
@@ -232,32 +234,55 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     const int n4 = XY >> 2;
     const bool prefetch = vec_ok && n4 <= kPackPrefetch * 64;
     const bool quick = g.fast && (X & 3) == 0 && XY >= 8 * Y;     // the x rows (8 B each) fit over the layer in LDS
+    const bool wide = vec_ok == 2;                  // layers and pointers are 16-byte aligned: four dwords per access
+    const int n16 = XY >> 4;
     uint32_t pre[kPackPrefetch];
-    if (prefetch && wave < g.Z) {
-        const uint32_t* s4 = reinterpret_cast<const uint32_t*>(src + env_vox + (size_t)wave * XY);
+    auto fetch_layer = [&](const uint8_t* layer) {
+        if (wide) {
+            const u32x4* s16 = reinterpret_cast<const u32x4*>(layer);
 #pragma unroll
-        for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? __builtin_nontemporal_load(&s4[u * 64 + lane]) : 0u;
-    }
+            for (int u = 0; u < kPackPrefetch / 4; ++u) {
+                u32x4 v = { 0u, 0u, 0u, 0u };
+                if (u * 64 + lane < n16) v = __builtin_nontemporal_load(&s16[u * 64 + lane]);
+                pre[4 * u] = v.x; pre[4 * u + 1] = v.y; pre[4 * u + 2] = v.z; pre[4 * u + 3] = v.w;
+            }
+        } else {
+            const uint32_t* s4 = reinterpret_cast<const uint32_t*>(layer);
+#pragma unroll
+            for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? __builtin_nontemporal_load(&s4[u * 64 + lane]) : 0u;
+        }
+    };
+    if (prefetch && wave < g.Z) fetch_layer(src + env_vox + (size_t)wave * XY);
 
     for (int k = wave; k < g.Z; k += waves) {
         const uint8_t* lsrc = src + env_vox + (size_t)k * XY;
         uint8_t* ldst = vox_dst + env_vox + (size_t)k * XY;
         if (prefetch) {
-            uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
-            uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
+            if (wide) {
+                u32x4* d16 = reinterpret_cast<u32x4*>(ldst);
+                u32x4* m16 = reinterpret_cast<u32x4*>(mine);
 #pragma unroll
-            for (int u = 0; u < kPackPrefetch; ++u) {
-                const int b = u * 64 + lane;
-                if (b < n4) {
-                    m4[b] = pre[u];
-                    if (copy) __builtin_nontemporal_store(pre[u], &d4[b]);
+                for (int u = 0; u < kPackPrefetch / 4; ++u) {
+                    const int b = u * 64 + lane;
+                    if (b < n16) {
+                        const u32x4 v = { pre[4 * u], pre[4 * u + 1], pre[4 * u + 2], pre[4 * u + 3] };
+                        m16[b] = v;
+                        if (copy) __builtin_nontemporal_store(v, &d16[b]);
+                    }
+                }
+            } else {
+                uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
+                uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
+#pragma unroll
+                for (int u = 0; u < kPackPrefetch; ++u) {
+                    const int b = u * 64 + lane;
+                    if (b < n4) {
+                        m4[b] = pre[u];
+                        if (copy) __builtin_nontemporal_store(pre[u], &d4[b]);
+                    }
                 }
             }
-            if (k + waves < g.Z) {
-                const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc + (size_t)waves * XY);
-#pragma unroll
-                for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? __builtin_nontemporal_load(&s4[u * 64 + lane]) : 0u;
-            }
+            if (k + waves < g.Z) fetch_layer(lsrc + (size_t)waves * XY);
         } else if (vec_ok) {
             const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc);
             uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
@@ -337,8 +362,11 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
     const size_t XY = (size_t)g.X * g.Y;
     const size_t layer_stride = (XY + 15) & ~(size_t)15;
     const size_t lds = layer_stride * (kPackThreads / 64);
-    const int vec_ok = (XY % 4 == 0) && ((reinterpret_cast<uintptr_t>(src) & 3) == 0) &&
-                       ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
+    // 0: byte access; 1: dword access; 2: 16-byte access to the layers (sizes and both pointers aligned)
+    int vec_ok = (XY % 4 == 0) && ((reinterpret_cast<uintptr_t>(src) & 3) == 0) &&
+                 ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
+    if (vec_ok && XY % 16 == 0 && ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(vox_dst)) & 15) == 0)
+        vec_ok = 2;
     if (XY / 4 <= 8 * 64)
         hipLaunchKernelGGL(pack_kernel<8>, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
                            g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I, heights);
@@ -594,7 +622,6 @@ __device__ __forceinline__ int ctz64_nonzero(uint64_t v)
 }
 
 typedef __attribute__((address_space(3))) const uint64_t* lds_u64_ptr;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_ptr;
 
 // a*b + c on the 24-bit multiplier (full rate); every product on this path fits 24 x 24 bits.
