@@ -33,9 +33,11 @@ GridLayout make_layout(int X, int Y, int Z)
     return g;
 }
 
+constexpr int kScanClasses = 16;        // (dominant axis) x (direction along u, v, z)
+
 static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
-// LDS map (bytes):  [4 scan-class records, 80 B each] | [sx: W floats][sy: H floats] |
+// LDS map (bytes):  [16 scan-class records, 80 B each] | [sx: W floats][sy: H floats] |
 //                   [colour table 7*(M+1) dwords] | bit rows
 // fast grids stage four row arrays (x, x mirrored, y, y mirrored) of `staged_layers` layers each; others stage
 // all x rows.
@@ -48,7 +50,7 @@ static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one,
 {
     LdsMap m{};
     size_t off = 0;
-    m.classes = (uint32_t)off; off += 4 * 80;
+    m.classes = (uint32_t)off; off += kScanClasses * 80;
     m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
     m.lut = (uint32_t)off;
     off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
@@ -470,27 +472,34 @@ __device__ __forceinline__ float safe_rcp(float d)
     return __builtin_amdgcn_fmed3f(__builtin_amdgcn_rcpf(d), -kBig, kBig);
 }
 
-// Constants of one scan class of one camera.  A class is (dominant horizontal axis, direction):
-// 0: +x, 1: -x, 2: +y, 3: -y.  u is the scan axis, v the other horizontal axis.  For the negative
-// directions the class works in mirrored coordinates u' = U - u against a bit-reversed copy of the
-// rows, so that inside the traversal every ray runs towards increasing bit positions.
+// Constants of one scan class of one camera.  A class is (dominant horizontal axis, direction along it,
+// direction along the other horizontal axis, vertical direction): class = 8*(y dominant) + 4*(u negative) +
+// 2*(v negative) + (z negative), so a ray picks every direction-dependent constant with one record load
+// instead of selecting each per ray.  u is the scan axis, v the other horizontal axis.  For negative u
+// the class works in mirrored coordinates u' = U - u against a bit-reversed copy of the rows, so that
+// inside the traversal every ray runs towards increasing bit positions.  v and z crossings are counted
+// without sign; the direction is folded into the address and index steps.
 struct alignas(16) ScanClass {
-    float Pu;           // camera coordinate along u (mirrored for classes 1, 3)
+    float Pu;           // camera coordinate along u (mirrored for negative u)
     float uexit;        // U - Pu: distance to the far side of the grid along u
-    float hi_v, lo_v;   // distances from the camera to the upper / lower plane of its cell along v
-    float nv_pos, nv_neg;   // v planes between the camera cell and the grid boundary, each direction
+    float dist_v;       // distance from the camera to the first v plane in this direction (>= 0)
+    float nv_max;       // v planes between the camera cell and the grid boundary in this direction
+    float dist_z;       // the same two along z (the grid is cut at the top solid layer)
+    float nz_max;
+    float Pu_err;       // what rounding took from the mirrored coordinate: (U - P) - Pu exactly, 0 if not mirrored
     int   addr0;        // LDS byte address of the camera's row in this class's row array
     int   i0;           // camera cell along u (mirrored)
-    int   zstride;      // bytes between rows of consecutive layers: 8 * V
     int   um1;          // U - 1
     int   idx0;         // voxel index of (mirrored cell 0, camera's v cell, camera's layer)
-    int   face_u;       // face code of a voxel found while scanning along the row
-    int   face_v;       // face code of a -v face (add 1 for +v)
     int   stride_u;     // voxel-index step per mirrored u cell: +-1 (x scans) or +-X (y scans)
-    int   stride_v;     // voxel-index step per v cell: X (x scans) or 1 (y scans)
-    int   zstride_neg;  // -zstride
-    float Pu_err;       // what rounding took from the mirrored coordinate: (U - P) - Pu exactly, 0 if not mirrored
-    int   pad[3];
+    int   stride_v;     // voxel-index step per v crossing: +-X (x scans) or +-1 (y scans)
+    int   stride_z;     // voxel-index step per z crossing: +-X*Y
+    int   sv;           // row-address step per v crossing: +-8 bytes
+    int   sz;           // row-address step per z crossing: +-8*V bytes
+    int   face_u;       // face code of a voxel found while scanning along the row
+    int   face_v;       // face code of a voxel entered through a v crossing
+    int   face_z;       // face code of a voxel entered through a z crossing
+    int   pad;
 };
 static_assert(sizeof(ScanClass) == 80, "scan class record must be 80 bytes");
 
@@ -621,6 +630,14 @@ __device__ __forceinline__ int ctz64_nonzero(uint64_t v)
     return (int)min(flo, 32u + fhi);
 }
 
+// all ones if the sign bit of x is set, zero otherwise (kept opaque so that "mask & constant" stays one AND)
+__device__ __forceinline__ uint32_t sign_mask(float x)
+{
+    uint32_t m;
+    asm("v_ashrrev_i32 %0, 31, %1" : "=v"(m) : "v"(x));
+    return m;
+}
+
 typedef __attribute__((address_space(3))) const uint64_t* lds_u64_ptr;
 typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_ptr;
 
@@ -641,19 +658,20 @@ __device__ __forceinline__ int mad24s(int a, int b_uniform, int c)
 
 // Row-scan traversal: DDA over the (v,z) rows the ray passes through, one 64-bit shift per row.
 // The loop has one exit (row holds a solid cell in range, or the ray leaves the grid).  It ends for
-// every input: each turn advances n_v or n_z, the crossing parameters |n|*dt + t0 never decrease, and
+// every input: each turn advances n_v or n_z, the crossing parameters n*dt + t0 never decrease, and
 // t_end is that same expression at the last plane of each axis, so t_out reaches t_end after at most
 // V + Z + 2 turns; a NaN anywhere makes the comparison false and ends it at once.
-// n_v and n_z count crossings with the sign of the direction, so that the cell is (v0 + n_v, kc + n_z).
-__device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz, float hi_z, float lo_z,
-                                          float nz_pos, float nz_neg, int XY)
+// n_v and n_z count crossings without sign: the cell is (v0 +- n_v, kc +- n_z), the signs sit in the class.
+__device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz)
 {
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
     const float dv = xm ? dy : dx;
-    // class = 2*(y dominant) + (direction negative); its record sits at 80*class from the start of the
-    // workgroup's dynamic LDS
-    const uint32_t qoff = (xm ? 0u : 160u) + (__float_as_uint(du) >> 31) * 80u;
+    // class record at 80*class from the start of the workgroup's dynamic LDS.  Along v and z a component
+    // of -0 counts as positive (the ray never crosses a plane of that axis, and the distance to the
+    // upper plane is never 0 inside the cell): adding +0 turns -0 into +0 and changes nothing else.
+    const uint32_t qoff = (xm ? 0u : 640u) + (sign_mask(du) & 320u) + (sign_mask(dv + 0.0f) & 160u) +
+                          (sign_mask(dz + 0.0f) & 80u);
     ScanClass c;
     {
         lds_u32x4_ptr rec = (lds_u32x4_ptr)(uintptr_t)(classes_addr + qoff);
@@ -663,20 +681,12 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 
     const float dua = fabsf(du);
     const float inv_u = safe_rcp(dua);
-    const float inv_v = safe_rcp(dv);
-    const float inv_z = safe_rcp(dz);
-    const float dt_v = fabsf(inv_v), dt_z = fabsf(inv_z);
-    const bool vneg = dv < 0.0f, zneg = dz < 0.0f;
-    // first crossing on an axis: (upper plane - P)/d if d > 0, (lower plane - P)/d otherwise: the distance
-    // to that plane (hi >= 0 >= lo) times |1/d|; d = -0 counts as positive, its reciprocal is +-huge either way
-    const float t0_v = fabsf(vneg ? c.lo_v : c.hi_v) * dt_v;
-    const float t0_z = fabsf(zneg ? lo_z : hi_z) * dt_z;
-    // leaving the grid: same |n|*dt + t0 expression as the crossings, so the comparison below is exact
-    const float t_end = vmin3(c.uexit * inv_u, fmaf(vneg ? c.nv_neg : c.nv_pos, dt_v, t0_v),
-                              fmaf(zneg ? nz_neg : nz_pos, dt_z, t0_z));
-    const int sv = vneg ? -8 : 8;
-    const int sz = zneg ? c.zstride_neg : c.zstride;
-    const float step_v = vneg ? -1.0f : 1.0f, step_z = zneg ? -1.0f : 1.0f;
+    const float dt_v = fabsf(safe_rcp(dv)), dt_z = fabsf(safe_rcp(dz));
+    // first crossing on an axis: the distance to the first plane in the ray's direction times |1/d|
+    const float t0_v = c.dist_v * dt_v;
+    const float t0_z = c.dist_z * dt_z;
+    // leaving the grid: same n*dt + t0 expression as the crossings, so the comparison below is exact
+    const float t_end = vmin3(c.uexit * inv_u, fmaf(c.nv_max, dt_v, t0_v), fmaf(c.nz_max, dt_z, t0_z));
 
     float t_v = t0_v, t_z = t0_z, n_v = 0.0f, n_z = 0.0f;
     uint32_t addr = (uint32_t)c.addr0;
@@ -697,11 +707,11 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
         i_last = i_to;                                                                        \
         if ((in_range != 0) | !(t_out < t_end)) break;                                        \
         const bool cv = t_v <= t_z;                                                           \
-        n_v += cv ? step_v : 0.0f;                                                            \
-        n_z += cv ? 0.0f : step_z;                                                            \
-        addr += cv ? sv : sz;                                                                 \
-        t_v = fmaf(fabsf(n_v), dt_v, t0_v);                                                   \
-        t_z = fmaf(fabsf(n_z), dt_z, t0_z);                                                   \
+        n_v += cv ? 1.0f : 0.0f;                                                              \
+        n_z += cv ? 0.0f : 1.0f;                                                              \
+        addr += (uint32_t)(cv ? c.sv : c.sz);                                                 \
+        t_v = fmaf(n_v, dt_v, t0_v);                                                          \
+        t_z = fmaf(n_z, dt_z, t0_z);                                                          \
     }
     int i_a = c.i0, i_b;
     for (;;) {                                  // two turns per trip: the cell index alternates registers
@@ -714,11 +724,11 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     // in_range is r moved up so that cell i_last sits at bit 63: its lowest set bit p is cell i_last - (63 - p)
     const int iu = i_last - 63 + ctz64_nonzero(in_range);                        // mirrored cell along u
     const bool along_row = ((uint32_t)r & 1u) == 0u;                            // not the row's entry cell
-    // the row was entered at the later of the last v crossing and the last z crossing (|n|-1; for n = 0
+    // the row was entered at the later of the last v crossing and the last z crossing (n-1; for n = 0
     // the expression is <= 0 because the first plane is at most one cell away).  Recomputed with one
     // fused operation each: "t_v - dt_v" would cancel badly for a camera that almost touches a plane.
-    const float tv_last = fmaf(fabsf(n_v) - 1.0f, dt_v, t0_v);
-    const float tz_last = fmaf(fabsf(n_z) - 1.0f, dt_z, t0_z);
+    const float tv_last = fmaf(n_v - 1.0f, dt_v, t0_v);
+    const float tz_last = fmaf(n_z - 1.0f, dt_z, t0_z);
     const bool via_z = tz_last >= tv_last;
     // A hit in the row's entry cell was entered through the later of the two crossings.  The camera's own
     // cell is never solid here (the caller handles that camera before tracing), so the only way to find
@@ -728,12 +738,12 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     // distance along u to the near face of the hit cell: the mirrored camera coordinate was rounded once,
     // which matters when the camera almost touches that face; its exact rounding error comes with the class
     const float t_u = (((float)iu - c.Pu) - c.Pu_err) * inv_u;
-    const int face_vz = via_z ? (zneg ? 5 : 4) : c.face_v + (vneg ? 1 : 0);
+    const int face_vz = via_z ? c.face_z : c.face_v;
     const int face = along_row ? c.face_u : face_vz;
     const float t = along_row ? t_u : t_in;
     // voxel index: the class record holds the index of (mirrored cell 0, camera's v cell, camera's layer)
-    // and the index steps per cell along u (mirroring folded into the sign) and v
-    const int idx = mad24s((int)n_z, XY, mad24((int)n_v, c.stride_v, mad24(iu, c.stride_u, c.idx0)));
+    // and the signed index steps per cell along u and per crossing along v and z
+    const int idx = mad24((int)n_z, c.stride_z, mad24((int)n_v, c.stride_v, mad24(iu, c.stride_u, c.idx0)));
     Hit h;
     h.idx = found ? idx : -1;       // face and t are only meaningful for idx >= 0; the caller substitutes the miss values
     h.face = face;
@@ -770,7 +780,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
     // LDS map, mirrors lds_map() on the host
     const uint32_t off_classes = 0;
-    const uint32_t off_scalars = 320;
+    const uint32_t off_scalars = kScanClasses * 80;
     const uint32_t off_lut = off_scalars + (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
     const uint32_t off_rows = off_lut + (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15);
     float* lds_sx = reinterpret_cast<float*>(lds + off_scalars);
@@ -860,15 +870,15 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             }
         }
     }
-    if (use_rows && threadIdx.x >= 64 && threadIdx.x < 68) {
+    if (use_rows && threadIdx.x >= 64 && threadIdx.x < 64 + kScanClasses) {
         const int q = threadIdx.x - 64;
-        const bool xmaj = q < 2, neg = q & 1;
+        const bool xmaj = q < 8, neg = q & 4, vneg = q & 2, zneg = q & 1;
         const int U = xmaj ? X : Y, V = xmaj ? Y : X;
         const float pu = xmaj ? P[0] : P[1], pv = xmaj ? P[1] : P[0];
         ScanClass c;
         c.Pu = neg ? (float)U - pu : pu;
         c.Pu_err = 0.0f;
-        c.pad[0] = c.pad[1] = c.pad[2] = 0;
+        c.pad = 0;
         if (neg) {                                         // exact error of the rounded difference (two-sum)
             const float a = (float)U, bneg = -pu;
             const float bb = __fsub_rn(c.Pu, a);
@@ -881,30 +891,30 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         // on the - side is found as an ordinary hit along the row (through its u face, at t = 0).
         if (neg && c.Pu == floorf(c.Pu) && c.i0 >= 1 && c.Pu < (float)U) c.i0 -= 1;
         const int j0 = min(max((int)floorf(pv), 0), V - 1);
-        c.hi_v = (float)(j0 + 1) - pv;
-        c.lo_v = (float)j0 - pv;
-        c.nv_pos = (float)(V - 1 - j0);
-        c.nv_neg = (float)j0;
+        // first plane along v: the upper plane of the camera's cell for rising v, the lower one otherwise
+        c.dist_v = fabsf((float)(vneg ? j0 : j0 + 1) - pv);
+        c.nv_max = (float)(vneg ? j0 : V - 1 - j0);
+        // along z (a rising ray of a camera above the solids leaves the cut grid at its first z plane: any
+        // positive distance will do, the top of its real cell is one)
+        c.dist_z = fabsf((float)(zneg ? kc : k0 + 1) - P[2]);
+        c.nz_max = (float)(zneg ? kc : zlim - 1 - kc);
         const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? sxw : 0) : 2 * sxw + (neg ? syw : 0));
         c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(kc * V + j0));
-        c.zstride = 8 * V;
+        c.sv = vneg ? -8 : 8;
+        c.sz = zneg ? -8 * V : 8 * V;
         c.um1 = U - 1;
         c.face_u = 2 * (xmaj ? 0 : 1) + (neg ? 1 : 0);
-        c.face_v = 2 * (xmaj ? 1 : 0);
+        c.face_v = 2 * (xmaj ? 1 : 0) + (vneg ? 1 : 0);
+        c.face_z = zneg ? 5 : 4;
         const int su = xmaj ? 1 : X;                       // voxel-index step per original u cell
+        const int sv_idx = xmaj ? X : 1;                   // and per v cell
         c.stride_u = neg ? -su : su;
-        c.stride_v = xmaj ? X : 1;
-        c.idx0 = kc * X * Y + j0 * c.stride_v + (neg ? (U - 1) * su : 0);
-        c.zstride_neg = -8 * V;
+        c.stride_v = vneg ? -sv_idx : sv_idx;
+        c.stride_z = zneg ? -X * Y : X * Y;
+        c.idx0 = kc * X * Y + j0 * sv_idx + (neg ? (U - 1) * su : 0);
         *reinterpret_cast<ScanClass*>(lds + off_classes + q * 80) = c;
     }
     __syncthreads();
-
-    // z constants are the same for every ray of the camera
-    // (hi_z: a rising ray of a camera above the solids leaves the cut grid at its first z plane: any positive
-    // distance will do, the top of its real cell is one)
-    const float hi_z = (float)(k0 + 1) - P[2], lo_z = (float)kc - P[2];
-    const float nz_pos = (float)(zlim - 1 - kc), nz_neg = (float)kc;
 
     // A camera inside a solid voxel (its own body is already gone) sees that voxel everywhere, at depth 0
     // with the "inside" face: one test per workgroup instead of one per ray.
@@ -997,7 +1007,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             if (cam_idx >= 0) {
                 h.idx = cam_idx; h.face = 6; h.t = 0.0f;
             } else {
-                h = trace_rows(lds_base + off_classes, d[0], d[1], d[2], hi_z, lo_z, nz_pos, nz_neg, X * Y);
+                h = trace_rows(lds_base + off_classes, d[0], d[1], d[2]);
             }
         } else if (FAST) {
             // cameras outside the grid, and worlds taller than the staged layers: the x rows in global memory,

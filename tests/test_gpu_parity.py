@@ -330,7 +330,7 @@ def _mini_spec(N, A, grid, W, H, M):
                                       ((40, 40, 16), 130, 70), ((33, 2, 31), 64, 8), ((70, 9, 5), 40, 24),
                                       ((64, 64, 6), 48, 32), ((9, 100, 4), 36, 20), ((63, 64, 3), 40, 24),
                                       ((64, 1, 2), 16, 16), ((1, 64, 2), 24, 8), ((17, 63, 9), 128, 72),
-                                      ((64, 64, 40), 64, 40), ((64, 64, 76), 32, 24)])
+                                      ((64, 64, 40), 64, 40), ((64, 64, 75), 32, 24)])
 def test_unstructured_worlds_odd_sizes_cameras_anywhere(lib, orc, grid, W, H):
     """Random occupancy (overhangs, no floor), cameras inside, outside and inside solids, image sizes
     that are not multiples of the tile or of four, grids whose voxel count is not a multiple of 32."""
