@@ -14,6 +14,7 @@
 #include "mv_internal.h"
 
 #include <math.h>
+#include <type_traits>
 
 namespace mv {
 
@@ -490,10 +491,12 @@ struct alignas(16) ScanClass {
     int   addr0;        // LDS byte address of the camera's row in this class's row array
     int   i0;           // camera cell along u (mirrored)
     int   um1;          // U - 1
-    int   idx0;         // voxel index of (mirrored cell 0, camera's v cell, camera's layer)
-    int   stride_u;     // voxel-index step per mirrored u cell: +-1 (x scans) or +-X (y scans)
-    int   stride_v;     // voxel-index step per v crossing: +-X (x scans) or +-1 (y scans)
-    int   stride_z;     // voxel-index step per z crossing: +-X*Y
+    // voxel index of the hit = idx0 + cell*stride_u + n_v*stride_v + n_z*stride_z, evaluated with three fused
+    // multiply-adds: every term and partial sum is an integer below 2^24 in magnitude, so float32 is exact
+    float idx0;         // voxel index of (mirrored cell 0, camera's v cell, camera's layer)
+    float stride_u;     // voxel-index step per mirrored u cell: +-1 (x scans) or +-X (y scans)
+    float stride_v;     // voxel-index step per v crossing: +-X (x scans) or +-1 (y scans)
+    float stride_z;     // voxel-index step per z crossing: +-X*Y
     int   sv;           // row-address step per v crossing: +-8 bytes
     int   sz;           // row-address step per z crossing: +-8*V bytes
     int   face_u;       // face code of a voxel found while scanning along the row
@@ -638,6 +641,14 @@ __device__ __forceinline__ uint32_t sign_mask(float x)
     return m;
 }
 
+// v & 1 as a 32-bit operation of its own (the compiler otherwise widens the test back to the 64-bit row)
+__device__ __forceinline__ uint32_t low_bit(uint32_t v)
+{
+    uint32_t b;
+    asm("v_and_b32 %0, 1, %1" : "=v"(b) : "v"(v));
+    return b;
+}
+
 typedef __attribute__((address_space(3))) const uint64_t* lds_u64_ptr;
 typedef __attribute__((address_space(3))) const u32x4* lds_u32x4_ptr;
 
@@ -723,7 +734,7 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 
     // in_range is r moved up so that cell i_last sits at bit 63: its lowest set bit p is cell i_last - (63 - p)
     const int iu = i_last - 63 + ctz64_nonzero(in_range);                        // mirrored cell along u
-    const bool along_row = ((uint32_t)r & 1u) == 0u;                            // not the row's entry cell
+    const bool along_row = low_bit((uint32_t)r) == 0u;                          // not the row's entry cell
     // the row was entered at the later of the last v crossing and the last z crossing (n-1; for n = 0
     // the expression is <= 0 because the first plane is at most one cell away).  Recomputed with one
     // fused operation each: "t_v - dt_v" would cancel badly for a camera that almost touches a plane.
@@ -737,13 +748,14 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const float t_in = vmax3(tv_last, tz_last, 0.0f);
     // distance along u to the near face of the hit cell: the mirrored camera coordinate was rounded once,
     // which matters when the camera almost touches that face; its exact rounding error comes with the class
-    const float t_u = (((float)iu - c.Pu) - c.Pu_err) * inv_u;
+    const float iu_f = (float)iu;
+    const float t_u = ((iu_f - c.Pu) - c.Pu_err) * inv_u;
     const int face_vz = via_z ? c.face_z : c.face_v;
     const int face = along_row ? c.face_u : face_vz;
     const float t = along_row ? t_u : t_in;
     // voxel index: the class record holds the index of (mirrored cell 0, camera's v cell, camera's layer)
     // and the signed index steps per cell along u and per crossing along v and z
-    const int idx = mad24((int)n_z, c.stride_z, mad24((int)n_v, c.stride_v, mad24(iu, c.stride_u, c.idx0)));
+    const int idx = (int)fmaf(n_z, c.stride_z, fmaf(n_v, c.stride_v, fmaf(iu_f, c.stride_u, c.idx0)));
     Hit h;
     h.idx = found ? idx : -1;       // face and t are only meaningful for idx >= 0; the caller substitutes the miss values
     h.face = face;
@@ -908,10 +920,10 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         c.face_z = zneg ? 5 : 4;
         const int su = xmaj ? 1 : X;                       // voxel-index step per original u cell
         const int sv_idx = xmaj ? X : 1;                   // and per v cell
-        c.stride_u = neg ? -su : su;
-        c.stride_v = vneg ? -sv_idx : sv_idx;
-        c.stride_z = zneg ? -X * Y : X * Y;
-        c.idx0 = kc * X * Y + j0 * sv_idx + (neg ? (U - 1) * su : 0);
+        c.stride_u = (float)(neg ? -su : su);
+        c.stride_v = (float)(vneg ? -sv_idx : sv_idx);
+        c.stride_z = (float)(zneg ? -X * Y : X * Y);
+        c.idx0 = (float)(kc * X * Y + j0 * sv_idx + (neg ? (U - 1) * su : 0));
         *reinterpret_cast<ScanClass*>(lds + off_classes + q * 80) = c;
     }
     __syncthreads();
@@ -929,6 +941,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const int waves = threads >> 6;
     const int lane = threadIdx.x & 63;
     const int lx = lane & 7, ly = lane >> 3, quad = lane & 3;
+    const int lane_pix = ly * p.W + lx;
+    const float* sx_lane = lds_sx + lx;
+    const float* sy_lane = lds_sy + ly;
     const int tile_begin = part * p.tiles_per_block;
     const int tile_end = min(tile_begin + p.tiles_per_block, p.tiles_per_obs);
     // per-observation bases: everything inside one observation is addressed with 32-bit offsets
@@ -980,55 +995,72 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     // traced in the previous trip, then traces its own tile, and only then shades and stores the previous
     // one, so that the global fetch hides behind a whole traversal.  (The request is issued in the trip that
     // consumes it: a value still in flight across the loop's back edge would be waited for there.)
-    int pend_idx = -1, pend_face = 255;
-    float pend_t = 0.0f;
-    uint32_t pend_pix = 0;
-    bool pend_active = false, pending = false;
-    for (int tile = tile_begin + wave; tile < tile_end; tile += waves) {
-        // lanes without a hit (idx -1 = 0xffffffff) read the last voxel and drop it later: no branch
-        const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
+    // The loop exists twice: once with the row scan alone (the common case), once with the other tracers,
+    // so that the values only those need are not kept in registers through the common loop.
+    auto run_tiles = [&](auto rows_only_tag) {
+        constexpr bool kRowsOnly = decltype(rows_only_tag)::value;
+        int pend_idx = -1, pend_face = 255;
+        float pend_t = 0.0f;
+        uint32_t pend_pix = 0;
+        bool pend_active = false, pending = false;
+        for (int tile = tile_begin + wave; tile < tile_end; tile += waves) {
+            // lanes without a hit (idx -1 = 0xffffffff) read the last voxel and drop it later: no branch
+            const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
 
-        const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
-        const int col = tx * kTile + lx, row = ty * kTile + ly;
-        // PACKED launches have W and H multiples of the tile size: every lane owns a pixel
-        const bool active = PACKED ? true : (col < p.W && row < p.H);
-        const int ccol = PACKED ? col : min(col, p.W - 1), crow = PACKED ? row : min(row, p.H - 1);
-
-        // a4: ray through the pixel centre, two fused multiply-adds per axis
-        const float sx = lds_sx[ccol], sy = lds_sy[crow];
-        float d[3];
-        d[0] = fmaf(sy, Ux, fmaf(sx, Rx, Fx));
-        d[1] = fmaf(sy, Uy, fmaf(sx, Ry, Fy));
-        d[2] = fmaf(sy, Uz, fmaf(sx, Rz, Fz));
-
-        // a5: traversal
-        Hit h;
-        if (use_rows) {
-            if (cam_idx >= 0) {
-                h.idx = cam_idx; h.face = 6; h.t = 0.0f;
+            const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
+            // PACKED launches have W and H multiples of the tile size: every lane owns a pixel, and its
+            // addresses are a per-lane constant plus a per-tile (wave-uniform) offset
+            bool active = true;
+            float sx, sy;
+            uint32_t pix;
+            if (PACKED) {
+                sx = sx_lane[tx * kTile];
+                sy = sy_lane[ty * kTile];
+                pix = (uint32_t)(lane_pix + (ty * p.W + tx) * kTile);
             } else {
-                h = trace_rows(lds_base + off_classes, d[0], d[1], d[2]);
+                const int col = tx * kTile + lx, row = ty * kTile + ly;
+                active = col < p.W && row < p.H;
+                const int ccol = min(col, p.W - 1), crow = min(row, p.H - 1);
+                sx = lds_sx[ccol];
+                sy = lds_sy[crow];
+                pix = (uint32_t)mad24s(crow, p.W, ccol);
             }
-        } else if (FAST) {
-            // cameras outside the grid, and worlds taller than the staged layers: the x rows in global memory,
-            // own body skipped by index
-            h = trace_generic(reinterpret_cast<const uint32_t*>(p.bits + (size_t)env * g.env_words), 2 * g.rowwords_x, P, d,
-                              X, Y, Z, origin_in_grid, p.max_steps, self_lo, self_hi);
-        } else {
-            h = trace_generic(reinterpret_cast<const uint32_t*>(lds_rows), 2 * g.rowwords_x, P, d, X, Y, Z,
-                              origin_in_grid, p.max_steps, -1, -1);
-        }
 
-        if (pending) shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
-        pend_idx = h.idx; pend_face = h.face; pend_t = h.t;
-        pend_pix = (uint32_t)mad24s(crow, p.W, ccol);
-        pend_active = active;
-        pending = true;
-    }
-    if (pending) {
-        const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
-        shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
-    }
+            // a4: ray through the pixel centre, two fused multiply-adds per axis
+            float d[3];
+            d[0] = fmaf(sy, Ux, fmaf(sx, Rx, Fx));
+            d[1] = fmaf(sy, Uy, fmaf(sx, Ry, Fy));
+            d[2] = fmaf(sy, Uz, fmaf(sx, Rz, Fz));
+
+            // a5: traversal
+            Hit h;
+            if (kRowsOnly) {
+                h = trace_rows(lds_base + off_classes, d[0], d[1], d[2]);
+            } else if (use_rows) {
+                h.idx = cam_idx; h.face = 6; h.t = 0.0f;
+            } else if (FAST) {
+                // cameras outside the grid, and worlds taller than the staged layers: the x rows in global
+                // memory, own body skipped by index
+                h = trace_generic(reinterpret_cast<const uint32_t*>(p.bits + (size_t)env * g.env_words), 2 * g.rowwords_x,
+                                  P, d, X, Y, Z, origin_in_grid, p.max_steps, self_lo, self_hi);
+            } else {
+                h = trace_generic(reinterpret_cast<const uint32_t*>(lds_rows), 2 * g.rowwords_x, P, d, X, Y, Z,
+                                  origin_in_grid, p.max_steps, -1, -1);
+            }
+
+            if (pending) shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
+            pend_idx = h.idx; pend_face = h.face; pend_t = h.t;
+            pend_pix = pix;
+            pend_active = active;
+            pending = true;
+        }
+        if (pending) {
+            const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
+            shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
+        }
+    };
+    if (use_rows && cam_idx < 0) run_tiles(std::true_type{});
+    else run_tiles(std::false_type{});
 }
 
 // ------------------------------------------------------------------------------------------
