@@ -21,9 +21,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E datasheet peak
-# Plain vector-ALU issue ceiling: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one lane-instruction per lane
-# and clock (the published 157.3 TFLOP/s fp32 vector figure counts an FMA as 2 and packed issue as 2).
-ALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # 39321.6 G lane-instructions/s
+# Vector-ALU peak: the published 157.3 TFLOP/s fp32 vector figure with a fused multiply-add counted as ONE
+# lane-instruction: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz.  Only the full-rate instructions (fma, add,
+# multiply, move, and, right shifts) can reach it; min/max, compares, selects, conversions and 64-bit shifts
+# issue at half of it (profiles/valu_instruction_rates.txt), and they are most of a ray traversal.
+ALU_PEAK_GOPS = 256 * 4 * 32 * 2.4     # 78643.2 G lane-instructions/s
 # Mean per-cell DDA steps per ray of the CPU oracle on camera set 0 of each workload (measured with the
 # oracle's step counter on the first 256/512/256/128 environments); the cpu_baseline leg re-measures it.
 ORACLE_MEAN_STEPS = {1: 8.75, 2: 8.98, 3: 8.45, 4: 10.20}
@@ -240,7 +242,7 @@ def main() -> int:
     alg_ops = algorithmic_lane_ops_per_ray(mean_steps) * rays_per_obs * n if mean_steps else None
     if alg_ops is not None:
         alu_achieved = alg_ops / (render_ms.mean() * 1e-3) / 1e9
-        # the render kernel issues vector instructions 95 % of the time: plain ALU arithmetic binds it
+        # plain vector arithmetic binds the render kernel (neither HBM nor LDS comes close, see below)
         result["roofline"] = {"bound": "alu", "kernel": "mv::render_kernel", "achieved": alu_achieved,
                               "peak": ALU_PEAK_GOPS, "unit": "G lane-instructions/s",
                               "frac": alu_achieved / ALU_PEAK_GOPS, "traffic": traffic,
