@@ -673,6 +673,11 @@ __device__ __forceinline__ int mad24s(int a, int b_uniform, int c)
 // t_end is that same expression at the last plane of each axis, so t_out reaches t_end after at most
 // V + Z + 2 turns; a NaN anywhere makes the comparison false and ends it at once.
 // n_v and n_z count crossings without sign: the cell is (v0 +- n_v, kc +- n_z), the signs sit in the class.
+// kNarrow: both horizontal grid sizes are below 64.  The parameter at which a row is left is capped at
+// t_end, which puts the last cell of the run at U at most (U only through rounding at the far boundary);
+// with U <= 63 that still is a valid bit position of an always-empty cell, and the clamp to U - 1 that
+// 64-cell rows need is left out.
+template <bool kNarrow>
 __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz)
 {
     const bool xm = fabsf(dx) >= fabsf(dy);
@@ -710,9 +715,9 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 #define MV_ROW_TURN(i_from, i_to)                                                             \
     {                                                                                         \
         const uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;                                   \
-        const float t_out = vmin(t_v, t_z);                                                   \
+        const float t_out = kNarrow ? vmin3(t_v, t_z, t_end) : vmin(t_v, t_z);                \
         const float u_out = fmaf(t_out, dua, c.Pu);                                           \
-        i_to = min((int)u_out, c.um1);                                                        \
+        i_to = kNarrow ? (int)u_out : min((int)u_out, c.um1);                                 \
         r = row >> (i_from);                                                                  \
         in_range = r << ((((i_to) ^ -1) + (i_from)) & 63);                                    \
         i_last = i_to;                                                                        \
@@ -997,8 +1002,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     // consumes it: a value still in flight across the loop's back edge would be waited for there.)
     // The loop exists twice: once with the row scan alone (the common case), once with the other tracers,
     // so that the values only those need are not kept in registers through the common loop.
-    auto run_tiles = [&](auto rows_only_tag) {
+    auto run_tiles = [&](auto rows_only_tag, auto narrow_tag) {
         constexpr bool kRowsOnly = decltype(rows_only_tag)::value;
+        constexpr bool kNarrow = decltype(narrow_tag)::value;
         int pend_idx = -1, pend_face = 255;
         float pend_t = 0.0f;
         uint32_t pend_pix = 0;
@@ -1035,7 +1041,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             // a5: traversal
             Hit h;
             if (kRowsOnly) {
-                h = trace_rows(lds_base + off_classes, d[0], d[1], d[2]);
+                h = trace_rows<kNarrow>(lds_base + off_classes, d[0], d[1], d[2]);
             } else if (use_rows) {
                 h.idx = cam_idx; h.face = 6; h.t = 0.0f;
             } else if (FAST) {
@@ -1059,8 +1065,12 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
         }
     };
-    if (use_rows && cam_idx < 0) run_tiles(std::true_type{});
-    else run_tiles(std::false_type{});
+    if (use_rows && cam_idx < 0) {
+        if (X < 64 && Y < 64) run_tiles(std::true_type{}, std::true_type{});
+        else run_tiles(std::true_type{}, std::false_type{});
+    } else {
+        run_tiles(std::false_type{}, std::false_type{});
+    }
 }
 
 // ------------------------------------------------------------------------------------------
