@@ -723,8 +723,9 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
         i_last = i_to;                                                                        \
         if ((in_range != 0) | !(t_out < t_end)) break;                                        \
         const bool cv = t_v <= t_z;                                                           \
-        n_v += cv ? 1.0f : 0.0f;                                                              \
-        n_z += cv ? 0.0f : 1.0f;                                                              \
+        const float one_v = cv ? 1.0f : 0.0f;                                                 \
+        n_v += one_v;                                                                         \
+        n_z += 1.0f - one_v;                                                                  \
         addr += (uint32_t)(cv ? c.sv : c.sz);                                                 \
         t_v = fmaf(n_v, dt_v, t0_v);                                                          \
         t_z = fmaf(n_z, dt_z, t0_z);                                                          \
