@@ -670,6 +670,48 @@ def test_partial_uploads_and_palette_keep(lib, orc):
     parity.compare(run.numpy(), ob.render(threads=8), label="after rejected calls")
 
 
+@pytest.mark.parametrize("grid", [(63, 9, 4), (64, 9, 4), (9, 63, 4), (9, 64, 4), (62, 63, 3), (40, 40, 5)])
+def test_rays_that_reach_the_far_end_of_a_row(lib, orc, grid):
+    """Rows of 63 cells and fewer are scanned without clamping the last cell of a run, rows of 64 cells
+    with the clamp: rays that run the whole length of a row, towards either end, with solids in the last
+    column, next to it, or nowhere, and cameras close to or on the near and far boundary."""
+    X, Y, Z = grid
+    rng = np.random.default_rng(X * 1000 + Y)
+    N, A, M = 6, 4, 5
+    spec = _mini_spec(N, A, grid, 48, 16, M)
+    vox = np.zeros((N, Z, Y, X), np.uint8)
+    for e in range(N):
+        if e % 3 == 0:                       # solids in the outermost columns only, at random rows and layers
+            for col in (0, X - 1):
+                vox[e, :, :, col] = np.where(rng.random((Z, Y)) < 0.5, rng.integers(1, M + 1, (Z, Y)), 0)
+            for row in (0, Y - 1):
+                vox[e, :, row, :] = np.where(rng.random((Z, X)) < 0.5, rng.integers(1, M + 1, (Z, X)), 0)
+        elif e % 3 == 1:                     # the column next to the outermost one
+            vox[e, :, :, X - 2] = rng.integers(0, M + 1, (Z, Y))
+            vox[e, :, :, 1] = rng.integers(0, M + 1, (Z, Y))
+            vox[e, :, Y - 2, :] = rng.integers(0, M + 1, (Z, X))
+        # e % 3 == 2: empty world, every ray leaves through the far side
+    pal = rng.integers(0, 256, (N, M + 1, 3)).astype(np.uint8)
+    cams = np.zeros((N * A, 5), np.float32)
+    for o in range(N * A):
+        towards = o % 4                      # +x, -x, +y, -y, each nearly parallel to the rows
+        yaw = (0.0, np.pi, np.pi / 2, -np.pi / 2)[towards] + rng.uniform(-0.02, 0.02)
+        near = rng.choice([0.0, 1e-3, 0.5, 1.0])
+        pos = [rng.uniform(0.1, X - 0.1), rng.uniform(0.1, Y - 0.1), rng.uniform(0.1, Z - 0.1)]
+        if towards == 0: pos[0] = near
+        if towards == 1: pos[0] = X - near
+        if towards == 2: pos[1] = near
+        if towards == 3: pos[1] = Y - near
+        cams[o] = (pos[0], pos[1], pos[2], yaw, rng.uniform(-0.02, 0.02))
+    hfov = 0.3
+    ob = _oracle_for(orc, spec, vox, pal, cams, hfov_rad=hfov)
+    run = _gpu_for(spec, vox, pal, cams, hfov_rad=hfov)
+    run.render()
+    g, ref = run.numpy(), ob.render()
+    _pixelwise_rule(g, ref, f"far end of rows, grid {grid}")
+    assert (ref.hit_index >= 0).any() and (ref.hit_index < 0).any()
+
+
 def test_largest_grid_the_lds_plan_takes(lib, orc):
     grid = (128, 128, 32)                   # 64 KiB of occupancy bits
     rng = np.random.default_rng(8)
