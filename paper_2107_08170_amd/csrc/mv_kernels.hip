@@ -835,12 +835,16 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         __hip_atomic_fetch_max(p.heights.host_max, ztop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 
-    {   // a3: stage pixel scalars, colour table and this environment's bit rows
-        for (int i = threadIdx.x; i < p.W; i += threads) lds_sx[i] = p.sx[i];
-        for (int i = threadIdx.x; i < p.H; i += threads) lds_sy[i] = p.sy[i];
+    {   // a3: stage pixel scalars, colour table and this environment's bit rows.
+        // The first loads of every stream are issued before any of them is consumed (clamped indices
+        // instead of branches keep them in one straight run, and a trip of the row loop fetches four
+        // words per thread): the staging then waits for one or two memory round trips instead of five.
+        const int tid = threadIdx.x;
         const uint32_t* gl = p.lut + (size_t)env * kNumFaces * p.materials_plus_one;
         uint32_t* ll = reinterpret_cast<uint32_t*>(lds + off_lut);
-        for (int i = threadIdx.x; i < kNumFaces * p.materials_plus_one; i += threads) ll[i] = gl[i];
+        const int lut_n = kNumFaces * p.materials_plus_one;
+        const float first_sx = p.sx[min(tid, p.W - 1)], first_sy = p.sy[min(tid, p.H - 1)];
+        const uint32_t first_lut = gl[min(tid, lut_n - 1)];
         const uint64_t* gb = p.bits + (size_t)env * g.env_words;
         if (FAST) {
             if (use_rows) {
@@ -849,20 +853,29 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 uint64_t* axm = ax + sxw;
                 uint64_t* ay = axm + sxw;
                 uint64_t* aym = ay + syw;
-                for (int w = threadIdx.x; w < sxw; w += threads) {
-                    uint64_t v = gb[w];
-                    ax[w] = v;
-                    axm[w] = __brevll(v) >> (64 - X);
-                }
-                for (int w = threadIdx.x; w < syw; w += threads) {
-                    uint64_t v = gb[g.xrow_words + w];
-                    ay[w] = v;
-                    aym[w] = __brevll(v) >> (64 - Y);
-                }
+                const uint64_t* gy = gb + g.xrow_words;
+                const int longest = sxw > syw ? sxw : syw;
+                auto row_trip = [&](int base) {
+                    const int w0 = base + tid, w1 = w0 + threads;
+                    const uint64_t x0 = gb[min(w0, sxw - 1)], x1 = gb[min(w1, sxw - 1)];
+                    const uint64_t y0 = gy[min(w0, syw - 1)], y1 = gy[min(w1, syw - 1)];
+                    if (w0 < sxw) { ax[w0] = x0; axm[w0] = __brevll(x0) >> (64 - X); }
+                    if (w1 < sxw) { ax[w1] = x1; axm[w1] = __brevll(x1) >> (64 - X); }
+                    if (w0 < syw) { ay[w0] = y0; aym[w0] = __brevll(y0) >> (64 - Y); }
+                    if (w1 < syw) { ay[w1] = y1; aym[w1] = __brevll(y1) >> (64 - Y); }
+                };
+                row_trip(0);                    // outside the loop: its loads join the three above
+                for (int base = 2 * threads; base < longest; base += 2 * threads) row_trip(base);
             }
         } else {
-            for (int w = threadIdx.x; w < g.xrow_words; w += threads) lds_rows[w] = gb[w];
+            for (int w = tid; w < g.xrow_words; w += threads) lds_rows[w] = gb[w];
         }
+        if (tid < p.W) lds_sx[tid] = first_sx;
+        if (tid < p.H) lds_sy[tid] = first_sy;
+        if (tid < lut_n) ll[tid] = first_lut;
+        for (int i = tid + threads; i < p.W; i += threads) lds_sx[i] = p.sx[i];
+        for (int i = tid + threads; i < p.H; i += threads) lds_sy[i] = p.sy[i];
+        for (int i = tid + threads; i < lut_n; i += threads) ll[i] = gl[i];
     }
     __syncthreads();
 
