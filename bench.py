@@ -53,7 +53,7 @@ def algorithmic_bytes_per_obs(spec) -> float:
 def measured_traffic(workload: str, column: int = 1):
     """Bytes per render launch from the committed rocprofv3 counter summary: column 1 = HBM (FETCH_SIZE and
     WRITE_SIZE scaled against a plain copy), column 2 = LDS (from SQ_INSTS_LDS); None when no summary covers
-    this workload."""
+    this workload.  Column 3 = vector lane-instructions executed per launch (SQ_INSTS_VALU x 64)."""
     path = os.path.join(ROOT, "profiles", "render_traffic.txt")
     try:
         with open(path) as f:
@@ -247,6 +247,11 @@ def main() -> int:
                               "peak": ALU_PEAK_GOPS, "unit": "G lane-instructions/s",
                               "frac": alu_achieved / ALU_PEAK_GOPS, "traffic": traffic,
                               "algorithmic_ops_per_launch": alg_ops, "oracle_mean_steps_per_ray": mean_steps}
+        executed = measured_traffic(spec.name, 3)
+        if executed is not None:
+            # what the kernel really executes (profiled counter), next to the model's count
+            result["roofline"]["executed_ops_per_launch"] = executed
+            result["roofline"]["executed_frac"] = executed / (render_ms.mean() * 1e-3) / 1e9 / ALU_PEAK_GOPS
     result["hbm_roofline"] = {"bound": "hbm", "kernel": "mv::render_kernel", "achieved": achieved,
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                               "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
