@@ -261,6 +261,13 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
         const uint8_t* lsrc = src + env_vox + (size_t)k * XY;
         uint8_t* ldst = vox_dst + env_vox + (size_t)k * XY;
         if (prefetch) {
+            // The private material copy is only ever read at voxels whose occupancy bit is set (the hit
+            // voxel of a ray), so a layer without any solid voxel is not copied: its old bytes stay behind
+            // bits that are all zero.
+            uint32_t any = 0;
+#pragma unroll
+            for (int u = 0; u < kPackPrefetch; ++u) any |= pre[u];
+            const bool store_copy = copy && __ballot(any != 0) != 0;
             if (wide) {
                 u32x4* d16 = reinterpret_cast<u32x4*>(ldst);
                 u32x4* m16 = reinterpret_cast<u32x4*>(mine);
@@ -270,7 +277,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
                     if (b < n16) {
                         const u32x4 v = { pre[4 * u], pre[4 * u + 1], pre[4 * u + 2], pre[4 * u + 3] };
                         m16[b] = v;
-                        if (copy) __builtin_nontemporal_store(v, &d16[b]);
+                        if (store_copy) __builtin_nontemporal_store(v, &d16[b]);
                     }
                 }
             } else {
@@ -281,7 +288,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
                     const int b = u * 64 + lane;
                     if (b < n4) {
                         m4[b] = pre[u];
-                        if (copy) __builtin_nontemporal_store(pre[u], &d4[b]);
+                        if (store_copy) __builtin_nontemporal_store(pre[u], &d4[b]);
                     }
                 }
             }
