@@ -875,30 +875,54 @@ def _read_device(ptr, nbytes):
 @pytest.mark.parametrize("grid", [(40, 40, 16), (7, 5, 3), (16, 16, 8), (64, 64, 4), (70, 3, 5), (3, 130, 2), (64, 64, 9),
                                   (48, 56, 10), (36, 20, 7)])
 def test_pack_kernel_bit_exact(lib, grid):
-    """Occupancy bit rows along x and along y, and the top solid layer, against NumPy."""
+    """Occupancy bit rows along x and along y, and the top solid layer, against NumPy: after a first upload,
+    after a single voxel set high up, and after re-uploads of lower and of taller worlds (empty layers at
+    and above the previous top are skipped by the kernel and must still read as zero)."""
     rng = np.random.default_rng(17)
     N = 6
     X, Y, Z = grid
+    batch = binding.Batch(N, 1, grid, 4, 16, 8)
+
+    def check(vox, top_is_exact=True):
+        torch.cuda.synchronize()
+        for env in range(N):
+            xp, xw, yp, yw, tp = batch.debug_occupancy(env)
+            assert xw == (X + 63) // 64 and yw == (Y + 63) // 64
+            occ = vox[env] != 0                                               # [Z,Y,X]
+            want_x = np.packbits(np.pad(occ, ((0, 0), (0, 0), (0, xw * 64 - X))), axis=-1, bitorder="little")
+            got_x = _read_device(xp, Z * Y * xw * 8).reshape(Z, Y, xw * 8)
+            np.testing.assert_array_equal(got_x, want_x)
+            occ_t = occ.transpose(0, 2, 1)                                    # [Z,X,Y]
+            want_y = np.packbits(np.pad(occ_t, ((0, 0), (0, 0), (0, yw * 64 - Y))), axis=-1, bitorder="little")
+            got_y = _read_device(yp, Z * X * yw * 8).reshape(Z, X, yw * 8)
+            np.testing.assert_array_equal(got_y, want_y)
+            layers = np.nonzero(occ.any(axis=(1, 2)))[0]
+            top = int(_read_device(tp, 4).view(np.int32)[0])
+            exact = int(layers.max()) + 1 if layers.size else 0
+            assert top == exact if top_is_exact else top >= exact
+
     vox, pal = synth.random_world(rng, N, grid, 0.3, 4)
     vox[3, Z // 2:] = 0                       # environment 3: empty upper half
     vox[N - 1] = 0                            # last environment: empty
-    batch = binding.Batch(N, 1, grid, 4, 16, 8)
     batch.upload_worlds(torch.from_numpy(vox).cuda(), torch.from_numpy(pal).cuda(), stream=_stream())
-    torch.cuda.synchronize()
-    for env in (0, 3, N - 1):
-        xp, xw, yp, yw, tp = batch.debug_occupancy(env)
-        assert xw == (X + 63) // 64 and yw == (Y + 63) // 64
-        occ = vox[env] != 0                                               # [Z,Y,X]
-        want_x = np.packbits(np.pad(occ, ((0, 0), (0, 0), (0, xw * 64 - X))), axis=-1, bitorder="little")
-        got_x = _read_device(xp, Z * Y * xw * 8).reshape(Z, Y, xw * 8)
-        np.testing.assert_array_equal(got_x, want_x)
-        occ_t = occ.transpose(0, 2, 1)                                    # [Z,X,Y]
-        want_y = np.packbits(np.pad(occ_t, ((0, 0), (0, 0), (0, yw * 64 - Y))), axis=-1, bitorder="little")
-        got_y = _read_device(yp, Z * X * yw * 8).reshape(Z, X, yw * 8)
-        np.testing.assert_array_equal(got_y, want_y)
-        layers = np.nonzero(occ.any(axis=(1, 2)))[0]
-        top = int(_read_device(tp, 4).view(np.int32)[0])
-        assert top == (int(layers.max()) + 1 if layers.size else 0)
+    check(vox)
+    # one voxel set in the top layer of the half-empty and of the empty environment
+    idx = ((Z - 1) * Y + (Y - 1)) * X + (X - 1)
+    batch.update_voxels(np.array([3, N - 1], np.int32), np.array([idx, idx], np.int32), np.array([2, 1], np.uint8))
+    vox[3].reshape(-1)[idx] = 2
+    vox[N - 1].reshape(-1)[idx] = 1
+    check(vox)
+    # lower worlds everywhere (the rows of the layers that were solid must be cleared), then taller ones again
+    for keep in (max(Z // 3, 1), Z, 0, max(Z // 2, 1)):
+        vox2, _ = synth.random_world(rng, N, grid, 0.3, 4)
+        vox2[:, keep:] = 0
+        vox2[1] = 0
+        batch.upload_worlds(torch.from_numpy(vox2).cuda(), None, stream=_stream())
+        check(vox2)
+        vox3, _ = synth.random_world(rng, 2, grid, 0.2, 4)      # partial upload from host memory
+        batch.upload_worlds(vox3, None, first_env=2)
+        vox2[2:4] = vox3
+        check(vox2)
 
 
 def test_camera_records_match_the_oracle(lib, orc):
