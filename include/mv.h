@@ -178,6 +178,35 @@ typedef struct {
 int mv_draw_bars(mv_batch* batch, uint8_t* rgb, const float* fraction, const mv_bar* bar,
                  int32_t src_is_device, void* hip_stream);
 
+/* One simulator step for the whole batch in a single call (paper App. A.1: a vectorised interface, one
+ * step for all N x M agents, with environments that reset on their own; Sec. 3.2: the state changes a
+ * little per step and the cameras move with the agents).  In stream order the call applies this step's
+ * voxel edits (mv_update_voxels), moves the cameras (mv_set_cameras), marks the environments whose
+ * episode ended with this step as inactive (mv_set_active with the flags inverted), renders every other
+ * environment (mv_render_batch without the aux outputs) and, if asked, paints the indicator bar
+ * (mv_draw_bars).  Every pointer in mv_step_inputs is DEVICE memory on the batch's device and is not
+ * validated; nothing is copied to the host, allocated or waited for, so the call can be captured in a
+ * HIP graph.  The caller resets a finished environment by uploading its next world (mv_upload_worlds with
+ * first_env, count) before the step in which it is no longer flagged.  The inactive set stays in force for
+ * later mv_render_batch / mv_draw_bars calls until mv_set_active or the next mv_step replaces it. */
+typedef struct {
+    int32_t        num_edits;      /* voxel edits of this step, >= 0                                   */
+    const int32_t* edit_env;       /* [num_edits] environment of each edit; may be NULL if num_edits == 0 */
+    const int32_t* edit_voxel;     /* [num_edits] linear voxel index                                   */
+    const uint8_t* edit_material;  /* [num_edits] new material id, 0 = empty                           */
+    const float*   cams;           /* [N*A, 5] (x, y, z, yaw, pitch), required                         */
+    const int32_t* self_voxel;     /* [N*A] own-body voxel or -1; NULL = none                          */
+    const uint8_t* done;           /* [N] non-zero = episode ended, do not render; NULL = render all   */
+    const float*   bar_fraction;   /* [N*A] filled share of the bar; NULL = no bar                     */
+    const mv_bar*  bar;            /* HOST pointer, read during the call; required if bar_fraction     */
+} mv_step_inputs;
+
+/* rgb, depth: as for mv_render_batch (device, caller-owned; frames of finished environments keep what
+ * the tensors held).  Errors: those of the calls it is made of (MV_ERR_ARG for a null or negative
+ * field, MV_ERR_STATE before every environment has a grid, MV_ERR_HIP); edits already enqueued when a
+ * later part fails are not undone. */
+int mv_step(mv_batch* batch, const mv_step_inputs* in, uint8_t* rgb, float* depth, void* hip_stream);
+
 /* Pinned (page-locked) host memory for CPU consumers of the observations (paper Sec. 3.2: the images can
  * stay on the GPU for a GPU learner; a CPU learner or a logger reads them back).  Copies into memory
  * from mv_host_alloc run asynchronously at full PCIe rate; plain malloc'd memory also works with

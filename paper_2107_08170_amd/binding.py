@@ -18,7 +18,7 @@ MV_OK, MV_ERR_ARG, MV_ERR_STATE, MV_ERR_RANGE, MV_ERR_CAPACITY, MV_ERR_HIP = 0, 
 FACE_INSIDE, FACE_MISS = 6, 255
 
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
-           "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_host_alloc", "mv_host_free",
+           "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_step", "mv_host_alloc", "mv_host_free",
            "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records",
            "mv_debug_set_staged_layers")
 
@@ -37,6 +37,13 @@ class MvBar(C.Structure):
     """Mirror of ``mv_bar``."""
     _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("width", C.c_int32), ("height", C.c_int32),
                 ("fill_rgb", C.c_uint8 * 3), ("empty_rgb", C.c_uint8 * 3), ("reserved", C.c_uint8 * 2)]
+
+
+class MvStepInputs(C.Structure):
+    """Mirror of ``mv_step_inputs``."""
+    _fields_ = [("num_edits", C.c_int32), ("edit_env", C.c_void_p), ("edit_voxel", C.c_void_p),
+                ("edit_material", C.c_void_p), ("cams", C.c_void_p), ("self_voxel", C.c_void_p),
+                ("done", C.c_void_p), ("bar_fraction", C.c_void_p), ("bar", C.POINTER(MvBar))]
 
 
 class MvError(RuntimeError):
@@ -67,6 +74,7 @@ def load_library():
     lib.mv_render_batch.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.mv_set_active.argtypes = [vp, vp, C.c_int32, vp]
     lib.mv_draw_bars.argtypes = [vp, vp, vp, C.POINTER(MvBar), C.c_int32, vp]
+    lib.mv_step.argtypes = [vp, C.POINTER(MvStepInputs), vp, vp, vp]
     lib.mv_host_alloc.argtypes = [C.POINTER(vp), C.c_size_t]
     lib.mv_host_free.argtypes = [vp]
     lib.mv_host_free.restype = None
@@ -204,6 +212,29 @@ class Batch:
         bar.empty_rgb[:] = [int(v) for v in empty_rgb]
         _check(load_library().mv_draw_bars(self._h, _as_ptr(rgb), _as_ptr(fraction), C.byref(bar),
                                            1 if _is_device(fraction) else 0, stream))
+
+    def step(self, cams, rgb, depth, edits=None, self_voxel=None, done=None, bar_fraction=None, bar=None,
+             stream: int = 0) -> None:
+        """One whole step from device tensors: ``edits`` = (env i32[n], voxel i32[n], material u8[n]) or None,
+        ``done`` u8[N] or None, ``bar`` = dict(x, y, width, height, fill_rgb, empty_rgb) with ``bar_fraction``
+        f32[N*A]."""
+        inp = MvStepInputs()
+        if edits is not None:
+            env, voxel, material = edits
+            inp.num_edits = int(env.shape[0])
+            inp.edit_env, inp.edit_voxel, inp.edit_material = _as_ptr(env), _as_ptr(voxel), _as_ptr(material)
+        inp.cams = _as_ptr(cams)
+        inp.self_voxel = _as_ptr(self_voxel)
+        inp.done = _as_ptr(done)
+        inp.bar_fraction = _as_ptr(bar_fraction)
+        c_bar = None
+        if bar is not None:
+            c_bar = MvBar()
+            c_bar.x, c_bar.y, c_bar.width, c_bar.height = bar["x"], bar["y"], bar["width"], bar["height"]
+            c_bar.fill_rgb[:] = [int(v) for v in bar["fill_rgb"]]
+            c_bar.empty_rgb[:] = [int(v) for v in bar["empty_rgb"]]
+            inp.bar = C.pointer(c_bar)
+        _check(load_library().mv_step(self._h, C.byref(inp), _as_ptr(rgb), _as_ptr(depth), stream))
 
     def fetch_observations(self, rgb_dev, depth_dev, first_obs: int, count: int, rgb_host, depth_host,
                            stream: int = 0) -> None:

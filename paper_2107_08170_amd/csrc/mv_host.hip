@@ -454,6 +454,33 @@ int mv_draw_bars(mv_batch* b, uint8_t* rgb, const float* fraction, const mv_bar*
     return MV_OK;
 }
 
+int mv_step(mv_batch* b, const mv_step_inputs* in, uint8_t* rgb, float* depth, void* hip_stream)
+{
+    if (!b || !in || !rgb || !depth) return fail(MV_ERR_ARG, "mv_step: null argument");
+    if (in->num_edits < 0) return fail(MV_ERR_ARG, "mv_step: num_edits = %d", in->num_edits);
+    if (in->num_edits > 0 && (!in->edit_env || !in->edit_voxel || !in->edit_material))
+        return fail(MV_ERR_ARG, "mv_step: %d edits without their arrays", in->num_edits);
+    if (!in->cams) return fail(MV_ERR_ARG, "mv_step: cams is null");
+    if (in->bar_fraction && !in->bar) return fail(MV_ERR_ARG, "mv_step: bar_fraction without bar");
+    int rc = MV_OK;
+    if (in->num_edits > 0)
+        rc = mv_update_voxels(b, in->num_edits, in->edit_env, in->edit_voxel, in->edit_material, 1, hip_stream);
+    if (rc == MV_OK) rc = mv_set_cameras(b, in->cams, in->self_voxel, 1, hip_stream);
+    if (rc == MV_OK) {
+        if (in->done) {
+            DeviceScope scope(b->cfg.device);
+            if (!scope.ok()) return fail(MV_ERR_HIP, "mv_step: cannot select device %d", b->cfg.device);
+            MV_HIP(mv::launch_active_from_done(in->done, b->d_active, b->cfg.num_envs, (hipStream_t)hip_stream));
+            b->all_active = false;
+        } else {
+            b->all_active = true;
+        }
+    }
+    if (rc == MV_OK) rc = mv_render_batch(b, rgb, depth, nullptr, nullptr, nullptr, hip_stream);
+    if (rc == MV_OK && in->bar_fraction) rc = mv_draw_bars(b, rgb, in->bar_fraction, in->bar, 1, hip_stream);
+    return rc;
+}
+
 int mv_host_alloc(void** out, size_t bytes)
 {
     if (!out || bytes == 0) return fail(MV_ERR_ARG, "mv_host_alloc: null pointer or zero size");

@@ -100,6 +100,8 @@ struct BarParams {
 };
 hipError_t launch_bars(uint8_t* rgb, const float* fraction, const uint8_t* active, int num_obs, int A, int W, int H,
                        const BarParams& bar, hipStream_t stream);
+// active[i] = (done[i] == 0) for the n environments of a batch
+hipError_t launch_active_from_done(const uint8_t* done, uint8_t* active, int n, hipStream_t stream);
 hipError_t prepare_render(size_t lds_bytes);
 hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t stream);
 

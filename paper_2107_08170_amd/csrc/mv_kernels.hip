@@ -1124,6 +1124,18 @@ hipError_t launch_bars(uint8_t* rgb, const float* fraction, const uint8_t* activ
     return hipGetLastError();
 }
 
+__global__ void active_from_done_kernel(const uint8_t* __restrict__ done, uint8_t* __restrict__ active, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) active[i] = done[i] == 0 ? 1 : 0;
+}
+
+hipError_t launch_active_from_done(const uint8_t* done, uint8_t* active, int n, hipStream_t stream)
+{
+    hipLaunchKernelGGL(active_from_done_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, done, active, n);
+    return hipGetLastError();
+}
+
 template <bool AUX, bool PACKED, bool FAST>
 static hipError_t set_lds_limit(size_t lds_bytes)
 {

@@ -93,6 +93,8 @@ def test_null_arguments(lib):
     assert lib.mv_set_cameras(None, None, None, 0, None) == binding.MV_ERR_ARG
     assert lib.mv_render_batch(None, None, None, None, None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_fetch_observations(None, None, None, 0, 1, None, None, None) == binding.MV_ERR_ARG
+    assert lib.mv_step(None, None, None, None, None) == binding.MV_ERR_ARG
+    assert lib.mv_step(None, C.byref(binding.MvStepInputs()), None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_host_alloc(None, 16) == binding.MV_ERR_ARG
     out = C.c_void_p()
     assert lib.mv_host_alloc(C.byref(out), 0) == binding.MV_ERR_ARG

@@ -805,6 +805,66 @@ def test_active_mask_and_indicator_bars(lib, orc):
     assert e.value.code == binding.MV_ERR_ARG
 
 
+def test_single_call_step_against_the_oracle(lib, orc):
+    """mv_step = edits + cameras + finished-episode flags + render + bar in one call, device inputs only:
+    three steps of the dynamic workload against the oracle; frames of finished environments keep what the
+    tensors held; the flags of one step do not leak into the next."""
+    wl = synth.generate(1, num_envs=12)
+    spec = wl.spec
+    rng = np.random.default_rng(5)
+    X, Y, Z = spec.grid
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
+    run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0], aux=False)
+    bar = dict(x=4, y=2, width=64, height=2, fill_rgb=(0, 255, 0), empty_rgb=(10, 10, 10))
+    vox = wl.voxels.copy()
+    for step in range(3):
+        # this step's edits: a few voxels per environment set or cleared (one edit per voxel)
+        n = 40
+        flat = rng.choice(spec.num_envs * X * Y * Z, size=n, replace=False)
+        env, idx = (flat // (X * Y * Z)).astype(np.int32), (flat % (X * Y * Z)).astype(np.int32)
+        mat = np.where(rng.random(n) < 0.5, 0, rng.integers(1, spec.num_materials + 1, size=n)).astype(np.uint8)
+        cams = synth.random_cameras(rng, spec.num_obs, spec.grid, margin=0.0, max_pitch=0.6)
+        selfv = None
+        if step == 2:                        # every camera stands in a body of its own (its cell and the one above)
+            cell = np.minimum(np.floor(cams[:, :3]).astype(np.int64), np.array([X - 1, Y - 1, Z - 1]))
+            selfv = ((cell[:, 2] * Y + cell[:, 1]) * X + cell[:, 0]).astype(np.int32)
+        done = (rng.random(spec.num_envs) < 0.3).astype(np.uint8) if step != 1 else None
+        fractions = rng.uniform(0, 1, size=spec.num_obs).astype(np.float32)
+        ob.update_voxels(env, idx, mat)
+        ob.set_cameras(cams, selfv)
+        ref = ob.render(threads=8)
+        active = np.ones(spec.num_envs, np.uint8) if done is None else (done == 0).astype(np.uint8)
+        want_rgb = ref.rgb.copy()
+        ob.draw_bars(want_rgb, fractions, active=active, **bar)
+        run.rgb.fill_(7)
+        run.depth.fill_(-1.0)
+        dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+        run.batch.step(dev(cams), run.rgb, run.depth, edits=(dev(env), dev(idx), dev(mat)), self_voxel=dev(selfv),
+                       done=dev(done), bar_fraction=dev(fractions), bar=bar, stream=_stream())
+        torch.cuda.synchronize()
+        rgb, depth = run.rgb.cpu().numpy(), run.depth.cpu().numpy()
+        obs_active = np.repeat(active.astype(bool), spec.agents_per_env)
+        assert (rgb[~obs_active] == 7).all() and (depth[~obs_active] == -1.0).all()
+        # depth and colours of the rendered frames: the parity rule without the side channels
+        tie = ref.edge_margin < parity.EDGE_MARGIN
+        ok = obs_active[:, None, None] & ~tie
+        assert ((ref.depth == 0) == (depth == 0))[ok].all(), f"step {step}"
+        assert (np.abs(depth - ref.depth)[ok] <= 1e-4 * np.abs(ref.depth)[ok]).all(), f"step {step}"
+        assert (np.abs(rgb.astype(int) - want_rgb.astype(int)).max(axis=-1)[ok] <= 1).all(), f"step {step}"
+        np.testing.assert_array_equal(rgb[obs_active][:, 2:4, 4:68], want_rgb[obs_active][:, 2:4, 4:68])
+        assert ok.mean() > 0.5
+    # without edits, flags and bar the call is cameras + render
+    run.batch.step(torch.from_numpy(wl.cameras[0]).cuda(), run.rgb, run.depth, stream=_stream())
+    torch.cuda.synchronize()
+    ob.set_cameras(wl.cameras[0], None)
+    ref = ob.render(threads=8)
+    ok = ~(ref.edge_margin < parity.EDGE_MARGIN)
+    assert (np.abs(run.depth.cpu().numpy() - ref.depth)[ok] <= 1e-4 * np.abs(ref.depth)[ok]).all()
+    with pytest.raises(binding.MvError) as e:
+        run.batch.step(None, run.rgb, run.depth)
+    assert e.value.code == binding.MV_ERR_ARG
+
+
 def test_step_replays_from_a_hip_graph(lib, orc):
     """The device-source calls enqueue kernels only (no allocation, no synchronisation, no memset), so a
     step can be captured once into a HIP graph and replayed: every replay, with fresh cameras and
