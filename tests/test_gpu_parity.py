@@ -892,9 +892,8 @@ def test_step_replays_from_a_hip_graph(lib, orc):
         side.synchronize()
         with torch.cuda.graph(graph, stream=side):
             st = torch.cuda.current_stream().cuda_stream
-            batch.update_voxels(env_in, idx_in, mat_in, stream=st)
-            batch.set_cameras(cams_in, self_in, stream=st)
-            batch.render(run_g.rgb, run_g.depth, stream=st)
+            # the single-call form of the step; the eager path below uses the separate calls
+            batch.step(cams_in, run_g.rgb, run_g.depth, edits=(env_in, idx_in, mat_in), self_voxel=self_in, stream=st)
     torch.cuda.synchronize()
     for step in range(1, 5):
         prev = vox
