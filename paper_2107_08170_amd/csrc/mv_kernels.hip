@@ -793,6 +793,10 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
     // XCD-aware mapping: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous range
     // of work items so that the blocks sharing an environment also share an L2.
+    // Staging runs at a raised wave priority (the tile loop at the default): a workgroup that has just
+    // arrived gets its few instructions issued ahead of the tracing waves it shares the SIMDs with, so its
+    // loads are on their way sooner and its wave slots start tracing earlier (render -1.8 % measured).
+    __builtin_amdgcn_s_setprio(3);
     const uint32_t b = blockIdx.x;
     const uint32_t work = (b % kXcds) * p.blocks_per_xcd + b / kXcds;
     if (work >= p.total_blocks) return;
@@ -1086,6 +1090,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
         }
     };
+    __builtin_amdgcn_s_setprio(0);
     if (use_rows && cam_idx < 0) {
         if (X < 64 && Y < 64) run_tiles(std::true_type{}, std::true_type{});
         else run_tiles(std::true_type{}, std::false_type{});
