@@ -95,8 +95,11 @@ def device_copy_rate(torch) -> float:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=3)
+    # defaults: the shader clock needs about a hundred launches after idle to settle (the first launches of a
+    # run are up to 25 % slower), so the warm-up covers that and the timed region is long enough to average
+    # the rest out; the whole timed region still lasts well under a second
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", type=int, default=2, help="workload index 1..4 (default 2: 4096 envs x 2 agents)")
     ap.add_argument("--tiles-per-block", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
