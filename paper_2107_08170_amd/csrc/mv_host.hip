@@ -380,6 +380,7 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     const int tiles_y = (p.H + mv::kTile - 1) / mv::kTile;
     p.tiles_per_obs = p.tiles_x * tiles_y;
     int tpb = b->cfg.tiles_per_block;
+    int tpb_tail = 0;                                   // 0: no shorter strips at the end of an XCD's work
     if (tpb <= 0) {
         // Strips of an observation per workgroup.  Two pulls: (1) enough workgroups to fill 256 CUs a few
         // times over (about 6144: on 1024 observations of 40x40x16 worlds, 6 strips per observation render
@@ -397,14 +398,27 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
         tpb = (int)((p.tiles_per_obs + strips - 1) / strips);
         const int min_tpb = waves * 2;
         if (tpb < min_tpb) tpb = min_tpb;
+        // The last twentieth of every XCD's observations is cut into strips a third as long: the XCD's
+        // work then ends with short workgroups (4096 x 2 observations, 3 strips of 48 tiles: tail strips of
+        // 16 tiles render 2.2 % faster than none; a tenth of the observations or strips of 24 or 12 tiles
+        // gain half of that).
+        tpb_tail = tpb / 3;
+        if (tpb_tail < min_tpb) tpb_tail = min_tpb;
+        if (tpb_tail >= tpb) tpb_tail = 0;
     }
     if (tpb > p.tiles_per_obs) tpb = p.tiles_per_obs;
     p.tiles_per_block = tpb;
     p.blocks_per_obs = (p.tiles_per_obs + tpb - 1) / tpb;
-    const unsigned long long total = (unsigned long long)p.blocks_per_obs * (unsigned long long)b->num_obs;
-    if (total > 0x7fffffffull - mv::kXcds) return fail(MV_ERR_CAPACITY, "mv_render_batch: too many workgroups");
-    p.total_blocks = (uint32_t)total;
-    p.blocks_per_xcd = (uint32_t)((total + mv::kXcds - 1) / mv::kXcds);
+    p.num_obs = b->num_obs;
+    p.obs_per_xcd = (b->num_obs + mv::kXcds - 1) / mv::kXcds;
+    const int tail_obs = tpb_tail > 0 ? p.obs_per_xcd / 20 : 0;
+    p.obs_body_per_xcd = p.obs_per_xcd - tail_obs;
+    p.tiles_per_block_tail = tail_obs > 0 ? tpb_tail : tpb;
+    p.blocks_per_obs_tail = (p.tiles_per_obs + p.tiles_per_block_tail - 1) / p.tiles_per_block_tail;
+    const unsigned long long per_xcd = (unsigned long long)p.obs_body_per_xcd * (unsigned long long)p.blocks_per_obs +
+                                       (unsigned long long)tail_obs * (unsigned long long)p.blocks_per_obs_tail;
+    if (per_xcd * mv::kXcds > 0x7fffffffull) return fail(MV_ERR_CAPACITY, "mv_render_batch: too many workgroups");
+    p.blocks_per_xcd = (uint32_t)per_xcd;
     p.sky_packed = (uint32_t)b->cfg.sky_rgb[0] | ((uint32_t)b->cfg.sky_rgb[1] << 8) | ((uint32_t)b->cfg.sky_rgb[2] << 16);
     p.max_steps = p.g.X + p.g.Y + p.g.Z + 3;
     MV_HIP(mv::launch_render(p, plan.bytes, (hipStream_t)hip_stream));

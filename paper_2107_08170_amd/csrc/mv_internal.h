@@ -62,8 +62,13 @@ struct RenderParams {
     int32_t voxels_per_env;
     int32_t W, H, A;
     int32_t materials_plus_one;
-    int32_t tiles_x, tiles_per_obs, tiles_per_block, blocks_per_obs;
-    uint32_t total_blocks, blocks_per_xcd;
+    int32_t tiles_x, tiles_per_obs;
+    // Work list: each XCD renders a contiguous range of obs_per_xcd observations, one workgroup per strip of
+    // tiles_per_block tiles; the last observations of the range (from obs_body_per_xcd on) are cut into
+    // shorter strips of tiles_per_block_tail tiles so that the XCD's last workgroups are short ones.
+    int32_t tiles_per_block, blocks_per_obs, tiles_per_block_tail, blocks_per_obs_tail;
+    int32_t num_obs, obs_per_xcd, obs_body_per_xcd;
+    uint32_t blocks_per_xcd;
     uint32_t sky_packed;
     int32_t max_steps;
     int32_t threads;                      // workgroup size (multiple of 64)

@@ -791,17 +791,33 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     // LDS byte address of the dynamic segment: row addresses in the scan-class records are absolute
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
 
-    // XCD-aware mapping: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous range
-    // of work items so that the blocks sharing an environment also share an L2.
-    // Staging runs at a raised wave priority (the tile loop at the default): a workgroup that has just
-    // arrived gets its few instructions issued ahead of the tracing waves it shares the SIMDs with, so its
-    // loads are on their way sooner and its wave slots start tracing earlier (render -1.8 % measured).
-    __builtin_amdgcn_s_setprio(3);
+    // XCD-aware mapping: hardware deals workgroup b to XCD b % 8; each XCD gets a contiguous range of
+    // observations so that the workgroups sharing an environment also share an L2.  Within the range the
+    // workgroups come strip by strip, observation by observation; the last observations are cut into
+    // shorter strips (an XCD's work then ends with short workgroups instead of long ones: a shorter tail).
     const uint32_t b = blockIdx.x;
-    const uint32_t work = (b % kXcds) * p.blocks_per_xcd + b / kXcds;
-    if (work >= p.total_blocks) return;
-    const int obs = (int)(work / (uint32_t)p.blocks_per_obs);
-    const int part = (int)(work - (uint32_t)obs * (uint32_t)p.blocks_per_obs);
+    const uint32_t xcd = b % kXcds, seq = b / kXcds;
+    const uint32_t body = (uint32_t)p.obs_body_per_xcd * (uint32_t)p.blocks_per_obs;
+    int obs, part, tiles_per_block, strips;
+    if (seq < body) {
+        obs = (int)(xcd * (uint32_t)p.obs_per_xcd + seq / (uint32_t)p.blocks_per_obs);
+        part = (int)(seq % (uint32_t)p.blocks_per_obs);
+        tiles_per_block = p.tiles_per_block;
+        strips = p.blocks_per_obs;
+    } else {
+        const uint32_t s2 = seq - body;
+        const uint32_t local = (uint32_t)p.obs_body_per_xcd + s2 / (uint32_t)p.blocks_per_obs_tail;
+        if (local >= (uint32_t)p.obs_per_xcd) return;
+        obs = (int)(xcd * (uint32_t)p.obs_per_xcd + local);
+        part = (int)(s2 % (uint32_t)p.blocks_per_obs_tail);
+        tiles_per_block = p.tiles_per_block_tail;
+        strips = p.blocks_per_obs_tail;
+    }
+    if (obs >= p.num_obs) return;
+    // The hardware deals an XCD's consecutive workgroups to its four shader engines in turn: with an even
+    // number of strips per observation the same engines would always get the top strips (mostly sky, the
+    // slow ones).  Rotating the strips by a hash of the observation index breaks that pairing.
+    if ((strips & 1) == 0) part = (int)(((uint32_t)part + (((uint32_t)obs * 2654435761u) >> 16)) % (uint32_t)strips);
     const int env = obs / p.A;
     if (p.active && p.active[env] == 0) return;         // finished episode: its frame is never drawn
     const GridLayout& g = p.g;
@@ -974,8 +990,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const int lane_pix = ly * p.W + lx;
     const float* sx_lane = lds_sx + lx;
     const float* sy_lane = lds_sy + ly;
-    const int tile_begin = part * p.tiles_per_block;
-    const int tile_end = min(tile_begin + p.tiles_per_block, p.tiles_per_obs);
+    const int tile_begin = part * tiles_per_block;
+    const int tile_end = min(tile_begin + tiles_per_block, p.tiles_per_obs);
     // per-observation bases: everything inside one observation is addressed with 32-bit offsets
     const size_t obs_pix = (size_t)obs * p.H * p.W;
     float* __restrict__ depth_obs = p.depth + obs_pix;
