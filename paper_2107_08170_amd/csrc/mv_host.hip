@@ -398,10 +398,10 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
         tpb = (int)((p.tiles_per_obs + strips - 1) / strips);
         const int min_tpb = waves * 2;
         if (tpb < min_tpb) tpb = min_tpb;
-        // The last twentieth of every XCD's observations is cut into strips a third as long: the XCD's
+        // The last twentieth (to tenth, see below) of every XCD's observations is cut into strips a third as long: the XCD's
         // work then ends with short workgroups (4096 x 2 observations, 3 strips of 48 tiles: tail strips of
-        // 16 tiles render 2.2 % faster than none; a tenth of the observations or strips of 24 or 12 tiles
-        // gain half of that).
+        // 16 tiles render 1 % faster than none, strips of 24 or 12 tiles gain less; 1024 x 4 observations:
+        // 3.6 % faster).
         tpb_tail = tpb / 3;
         if (tpb_tail < min_tpb) tpb_tail = min_tpb;
         if (tpb_tail >= tpb) tpb_tail = 0;
@@ -411,7 +411,16 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.blocks_per_obs = (p.tiles_per_obs + tpb - 1) / tpb;
     p.num_obs = b->num_obs;
     p.obs_per_xcd = (b->num_obs + mv::kXcds - 1) / mv::kXcds;
-    const int tail_obs = tpb_tail > 0 ? p.obs_per_xcd / 20 : 0;
+    // how much of the range: a twentieth when the launch runs a dozen or more rounds of workgroups through the
+    // chip, up to a tenth when it runs only a few (measured optimum on 1024 and 4096 observations: a tenth)
+    long long per_cu = (long long)(mv::kLdsBudget / plan.bytes);
+    if (per_cu > 32 / (p.threads / 64)) per_cu = 32 / (p.threads / 64);
+    if (per_cu < 1) per_cu = 1;
+    const long long rounds = (long long)p.blocks_per_obs * b->num_obs / (256 * per_cu);
+    int tail_den = (int)(rounds * 5 / 3);
+    if (tail_den < 10) tail_den = 10;
+    if (tail_den > 20) tail_den = 20;
+    const int tail_obs = tpb_tail > 0 ? p.obs_per_xcd / tail_den : 0;
     p.obs_body_per_xcd = p.obs_per_xcd - tail_obs;
     p.tiles_per_block_tail = tail_obs > 0 ? tpb_tail : tpb;
     p.blocks_per_obs_tail = (p.tiles_per_obs + p.tiles_per_block_tail - 1) / p.tiles_per_block_tail;
