@@ -719,9 +719,10 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     // it.  The second shift count is 63 - (i_to - i_from) = (i_from + ~i_to) mod 64: one xor-add, the
     // shifter ignores the upper bits.  Nothing after the loop needs i_from: the hit cell follows from
     // the lowest set bit of in_range and i_to, and bit 0 of r tells whether it is the row's entry cell.
+    // The next row is requested as soon as its address is known, at the end of the turn before (render -1 %).
+    uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;
 #define MV_ROW_TURN(i_from, i_to)                                                             \
     {                                                                                         \
-        const uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;                                   \
         const float t_out = kNarrow ? vmin3(t_v, t_z, t_end) : vmin(t_v, t_z);                \
         const float u_out = fmaf(t_out, dua, c.Pu);                                           \
         i_to = kNarrow ? (int)u_out : min((int)u_out, c.um1);                                 \
@@ -734,6 +735,7 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
         n_v += one_v;                                                                         \
         n_z += 1.0f - one_v;                                                                  \
         addr += (uint32_t)(cv ? c.sv : c.sz);                                                 \
+        row = *(lds_u64_ptr)(uintptr_t)addr;                                                  \
         t_v = fmaf(n_v, dt_v, t0_v);                                                          \
         t_z = fmaf(n_z, dt_z, t0_z);                                                          \
     }
