@@ -12,9 +12,6 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libmv.so")
-# measurement tool (vector instruction issue rates behind the ALU roofline); not loaded by the library
-RATES_SRC = os.path.join(PKG_DIR, "csrc", "valu_rates.hip")
-RATES_EXE = os.path.join(PKG_DIR, "valu_rates")
 SOURCES = ("csrc/mv_host.hip", "csrc/mv_kernels.hip")
 HEADERS = ("csrc/mv_internal.h", "../include/mv.h")
 
@@ -34,7 +31,7 @@ def is_stale() -> bool:
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every HIP source for gfx950: libmv.so and the valu_rates tool (always recompiles)."""
+    """Compile every HIP source for gfx950 into libmv.so (always recompiles)."""
     cmd = [_hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            # packed-FP32 instructions are kept out of the generated code on purpose
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -50,15 +47,6 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and proc.stderr:
         sys.stderr.write(proc.stderr)
-    tool = [_hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950",
-            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-Wall", "-Wno-unused-command-line-argument", "-o", RATES_EXE, RATES_SRC]
-    if verbose:
-        print(" ".join(tool), flush=True)
-    proc = subprocess.run(tool, capture_output=True, text=True)
-    if proc.returncode != 0:
-        sys.stderr.write(proc.stdout + proc.stderr)
-        raise RuntimeError("hipcc failed (valu_rates)")
     return LIB_PATH
 
 
