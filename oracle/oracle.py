@@ -51,6 +51,10 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
+    other = os.environ.get("MV_ORACLE_LIBRARY")     # another build of the same sources (the sanitizer test's)
+    if other:
+        _lib = _bind(C.CDLL(other))
+        return _lib
     build()
     _lib = _bind(C.CDLL(_LIB_PATH))
     return _lib

@@ -167,13 +167,13 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     b->materials_plus_one = cfg->num_materials + 1;
     b->tan_half_x = std::tan(0.5 * (double)cfg->hfov_rad);
     b->tan_half_y = b->tan_half_x * (double)cfg->height / (double)cfg->width;
-    // Face intensities are batch constants: ambient + diffuse * max(0, n.L) for the six axis
-    // normals (0:-x 1:+x 2:-y 3:+y 4:-z 5:+z), ambient alone for "inside".
-    const double L[3] = { lx / ln, ly / ln, lz / ln };
+    // Face intensities are batch constants (flat Lambert shading): every face code has an outward unit
+    // normal, and a face is lit by ambient + diffuse * (how far its normal leans towards the light); faces
+    // turned away from the light, and the "inside" code, get the ambient term alone.
+    static const signed char kNormal[6][3] = { { -1, 0, 0 }, { 1, 0, 0 }, { 0, -1, 0 }, { 0, 1, 0 }, { 0, 0, -1 }, { 0, 0, 1 } };
     for (int f = 0; f < 6; ++f) {
-        double ndotl = (f & 1) ? L[f >> 1] : -L[f >> 1];
-        if (ndotl < 0.0) ndotl = 0.0;
-        b->intensity[f] = (float)((double)cfg->ambient + (double)cfg->diffuse * ndotl);
+        const double lean = ((double)kNormal[f][0] * lx + (double)kNormal[f][1] * ly + (double)kNormal[f][2] * lz) / ln;
+        b->intensity[f] = (float)((double)cfg->ambient + (lean > 0.0 ? (double)cfg->diffuse * lean : 0.0));
     }
     b->intensity[6] = cfg->ambient;
     b->env_has_grid.assign((size_t)cfg->num_envs, 0);

@@ -574,3 +574,120 @@ def test_edge_margin_flags_ties_at_the_grid_boundary(orc):
     assert out.edge_margin[0, 0, 0] < 5e-5 and out.edge_margin[1, 0, 0] < 5e-5
     assert hit[2] == -1 and out.edge_margin[2, 0, 0] > 0.01             # clear miss
     assert hit[3] == (1 * 8 + 6) * 8 + 7 and out.edge_margin[3, 0, 0] > 0.01   # clear hit
+
+
+def _margin_by_plane_enumeration(P, d, t_begin, t_end, dims):
+    """The margin side channel written out from its definition, with no traversal: every integer plane of every
+    axis that the ray reaches at a parameter t_begin <= t <= t_end (t > 0) is a crossing; at each crossing, the
+    distance from the crossing point to the nearest integer along each of the two OTHER axes; the minimum over
+    all of them."""
+    best = np.inf
+    for a in range(3):
+        if d[a] == 0.0:
+            continue
+        for plane in range(0, dims[a] + 1):
+            t = (plane - P[a]) / d[a]
+            if not (t > 0.0 and t_begin * (1 - 1e-12) <= t <= t_end * (1 + 1e-12)):
+                continue
+            for o in range(3):
+                if o == a:
+                    continue
+                q = P[o] + t * d[o]
+                best = min(best, abs(q - np.rint(q)))
+    return best
+
+
+def test_edge_margin_equals_plane_enumeration(orc):
+    """edge_margin against its definition, enumerated plane by plane in Python: random small worlds, cameras
+    inside and outside the grid, every pixel.  The crossings run from the one that takes the ray into the grid
+    (cameras outside) up to the hit, or for a miss up to and including the crossing through the grid boundary.
+    A margin that skips crossings, uses the wrong axes or the wrong parameter differs on almost every pixel."""
+    rng = np.random.default_rng(77)
+    w, h = 16, 9
+    checked = outside_checked = 0
+    for trial in range(8):
+        grid = (int(rng.integers(3, 9)), int(rng.integers(3, 9)), int(rng.integers(2, 5)))
+        vox, pal = synth.random_world(rng, 1, grid, float(rng.uniform(0.02, 0.2)), 3)
+        cams = synth.random_cameras(rng, 2, grid, margin=0.0)
+        cams[:, :3] = np.clip(cams[:, :3], 0.05, np.array(grid, np.float32) - 0.05)
+        if trial >= 4:                        # outside the grid, looking roughly at its centre
+            away = rng.uniform(0.3, 2.0)
+            cams[:, 0] = -away
+            cams[:, 3] = rng.uniform(-0.5, 0.5, 2)
+        b, out = _single(orc, grid, vox[0], pal[0], cams, w=w, h=h)
+        for a in range(2):
+            P = b.camera_record(a)[:3].astype(np.float64)
+            rays = b.pixel_rays(a).astype(np.float64)
+            for r in range(h):
+                for c in range(w):
+                    d = rays[r, c]
+                    lo = [min((0.0 - P[k]) / d[k], (grid[k] - P[k]) / d[k]) for k in range(3) if d[k] != 0.0]
+                    hi = [max((0.0 - P[k]) / d[k], (grid[k] - P[k]) / d[k]) for k in range(3) if d[k] != 0.0]
+                    t_begin, t_exit = max(max(lo), 0.0), min(hi)
+                    got = out.edge_margin[a, r, c]
+                    if t_begin > t_exit:                                     # never enters the grid: no crossing
+                        assert got == np.inf and out.hit_index[a, r, c] == -1
+                        continue
+                    if out.hit_index[a, r, c] >= 0:
+                        if out.steps[a, r, c] == 0 and t_begin == 0.0:
+                            assert got == np.inf                             # camera inside a solid: no crossing
+                            continue
+                        t_end = out.t[a, r, c]
+                    else:
+                        t_end = t_exit
+                    want = _margin_by_plane_enumeration(P, d, t_begin, t_end, grid)
+                    if want < 1e-9:                                          # exact ties: order of crossings is open
+                        continue
+                    assert abs(got - want) <= 1e-9, (trial, a, r, c, got, want)
+                    checked += 1
+                    outside_checked += int(t_begin > 0.0)
+    assert checked > 1500 and outside_checked > 300
+
+
+def test_edge_margin_flags_a_grazed_edge_inside_the_grid(orc):
+    """A ray that only grazes a voxel edge in the MIDDLE of its path and then goes on to a clear hit is a tie as
+    well: turned a hair one way it enters the pillar, turned the other way it passes the pillar's corner and hits
+    the far wall.  Both must carry a margin below 5e-5 (for the second the near-tie is an early crossing, not the
+    last one); rays aimed well to either side keep a large margin."""
+    grid = (8, 8, 4)
+    vox = np.zeros((4, 8, 8), np.uint8)
+    vox[1, 3, 4] = 1                      # pillar voxel (i=4, j=3): its corner (x=4, y=4) is the grazed edge
+    vox[1, :, 7] = 2                      # far wall x = 7
+    pal = np.full((3, 3), 100, np.uint8)
+    px, py = 1.3, 1.7
+    yaw = np.arctan2(4.0 - py, 4.0 - px)
+    cams = np.array([[px, py, 1.5, yaw - 4e-6, 0.0], [px, py, 1.5, yaw + 4e-6, 0.0],
+                     [px, py, 1.5, yaw - 0.15, 0.0], [px, py, 1.5, yaw + 0.11, 0.0]], np.float32)
+    b = orc.OracleBatch(1, 4, grid, 1, 1, 2)
+    b.upload_worlds(vox[None], pal[None])
+    b.set_cameras(cams)
+    out = b.render()
+    hit, mat = out.hit_index[:, 0, 0], out.material[:, 0, 0]
+    pillar = (1 * 8 + 3) * 8 + 4
+    assert hit[0] == pillar and mat[1] == 2, (hit, mat)                  # one enters the pillar, one reaches the wall
+    assert out.edge_margin[0, 0, 0] < 5e-5 and out.edge_margin[1, 0, 0] < 5e-5, out.edge_margin[:, 0, 0]
+    assert out.steps[1, 0, 0] > out.steps[0, 0, 0] + 2                   # the graze is not the wall ray's last crossing
+    assert hit[2] == pillar and out.edge_margin[2, 0, 0] > 0.01          # clear hit on the pillar
+    assert mat[3] == 2 and out.edge_margin[3, 0, 0] > 0.01               # clear pass
+
+
+def test_single_pixel_entry_point_equals_the_full_render(orc):
+    """mvo_render_pixels (chosen pixels one by one, used for sampled comparisons at full batch size) returns,
+    field by field, what mvo_render holds at the same (observation, row, column)."""
+    wl = synth.generate(0)
+    s = wl.spec
+    b = orc.OracleBatch(s.num_envs, s.agents_per_env, s.grid, s.width, s.height, s.num_materials)
+    b.upload_worlds(wl.voxels, wl.palette)
+    b.set_cameras(wl.cameras[0])
+    full = b.render()
+    rng = np.random.default_rng(5)
+    n = 4000
+    obs = rng.integers(0, s.num_obs, n).astype(np.int32)
+    row = rng.integers(0, s.height, n).astype(np.int32)
+    col = rng.integers(0, s.width, n).astype(np.int32)
+    row[:4], col[:4] = [0, 0, s.height - 1, s.height - 1], [0, s.width - 1, 0, s.width - 1]
+    px = b.render_pixels(obs, row, col)
+    for name in ("rgb", "depth", "material", "hit_index", "face", "steps", "edge_margin", "t"):
+        np.testing.assert_array_equal(getattr(px, name), getattr(full, name)[obs, row, col], err_msg=name)
+    with pytest.raises(ValueError):
+        b.render_pixels(np.array([s.num_obs], np.int32), np.array([0], np.int32), np.array([0], np.int32))

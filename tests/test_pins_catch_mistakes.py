@@ -55,6 +55,12 @@ MISTAKES = [
     ("sky colour channels reversed", "mv_oracle.c", "out->rgb[0] = b->cfg.sky_rgb[0];", "out->rgb[0] = b->cfg.sky_rgb[2];"),
     ("bar width truncated", "mv_oracle.c", "volatile float sum = prod + 0.5f;\n        float cols", "volatile float sum = prod;\n        float cols"),
     ("edits land one voxel further", "mv_oracle.c", "(size_t)voxel_index[e]] = material[e];", "(size_t)voxel_index[e] + 1] = material[e];"),
+    ("margin: the crossing's own axis not skipped", "mv_oracle.c", "        if (a == axis) continue;\n        double q = P[a] + t * d[a];",
+     "        double q = P[a] + t * d[a];"),
+    ("margin: crossing point from the wrong direction component", "mv_oracle.c", "double q = P[a] + t * d[a];", "double q = P[a] + t * d[axis];"),
+    ("margin: only the last crossing counts", "mv_oracle.c", "if (m < out->edge_margin) out->edge_margin = m;", "out->edge_margin = m;"),
+    ("margin: the crossing into the grid forgotten", "mv_oracle.c", "out->edge_margin = crossing_margin(P, d, t0, entry_axis);", ""),
+    ("step counter counts every other crossing", "mv_oracle.c", "out->steps += 1;", "out->steps += (cell[axis] & 1);"),
     ("brute force keeps the farthest voxel", "mv_definition.c", "if (t_enter < best_t) {", "if (best_idx < 0 || t_enter > best_t) {"),
     ("brute force ignores rays leaving the slab", "mv_definition.c", "if (t_enter > t_leave || t_enter < 0.0) continue;", "if (t_enter < 0.0) continue;"),
 ]
@@ -83,6 +89,11 @@ def _battery(orc):
     yield lambda: pins.test_exact_zero_direction_components(orc)
     yield lambda: pins.test_sparse_edits_equal_a_fresh_upload(orc)
     yield lambda: pins.test_indicator_bar_closed_form(orc)
+    yield lambda: pins.test_edge_margin_flags_ties_at_the_grid_boundary(orc)
+    yield lambda: pins.test_edge_margin_equals_plane_enumeration(orc)
+    yield lambda: pins.test_edge_margin_flags_a_grazed_edge_inside_the_grid(orc)
+    yield lambda: pins.test_step_count_and_termination_bound(orc)
+    yield lambda: pins.test_single_pixel_entry_point_equals_the_full_render(orc)
 
 
 def _first_failure(orc):
