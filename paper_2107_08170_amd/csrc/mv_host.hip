@@ -102,6 +102,130 @@ static void free_batch(mv_batch* b)
     delete b;
 }
 
+// Field checks shared by every call that takes a configuration; `who` prefixes the message.  On success
+// *plan_out holds the LDS plan with all Z layers staged.
+static int check_config(const mv_config* cfg, const char* who, mv::GridLayout* layout_out, mv::LdsPlan* plan_out)
+{
+    if (cfg->num_envs <= 0 || cfg->agents_per_env <= 0)
+        return fail(MV_ERR_ARG, "%s: num_envs and agents_per_env must be positive", who);
+    if (cfg->grid_x <= 0 || cfg->grid_y <= 0 || cfg->grid_z <= 0)
+        return fail(MV_ERR_ARG, "%s: grid dimensions must be positive", who);
+    if (cfg->width <= 0 || cfg->height <= 0 || cfg->width > 16384 || cfg->height > 16384)
+        return fail(MV_ERR_ARG, "%s: image size must be in 1..16384", who);
+    if (!(cfg->hfov_rad > 0.0f) || !(cfg->hfov_rad < 3.14159f))
+        return fail(MV_ERR_ARG, "%s: hfov_rad must lie in (0, pi)", who);
+    if (cfg->num_materials < 1 || cfg->num_materials > 255)
+        return fail(MV_ERR_ARG, "%s: num_materials must be in 1..255", who);
+    if (cfg->reserved0 != 0) return fail(MV_ERR_ARG, "%s: reserved0 must be 0", who);
+    if (cfg->tiles_per_block < 0) return fail(MV_ERR_ARG, "%s: tiles_per_block must be >= 0", who);
+    if (cfg->device < 0) return fail(MV_ERR_ARG, "%s: device must be >= 0", who);
+    const double lx = cfg->light_dir[0], ly = cfg->light_dir[1], lz = cfg->light_dir[2];
+    const double ln = std::sqrt(lx * lx + ly * ly + lz * lz);
+    if (!(ln > 0.0) || !std::isfinite(ln)) return fail(MV_ERR_ARG, "%s: light_dir must be finite and non-zero", who);
+    if (!std::isfinite(cfg->ambient) || !std::isfinite(cfg->diffuse))
+        return fail(MV_ERR_ARG, "%s: ambient/diffuse must be finite", who);
+
+    const long long voxels = (long long)cfg->grid_x * cfg->grid_y * cfg->grid_z;
+    if (voxels > (1ll << 30)) return fail(MV_ERR_CAPACITY, "%s: grid too large", who);
+    const long long num_obs = (long long)cfg->num_envs * cfg->agents_per_env;
+    if (num_obs > (1ll << 24)) return fail(MV_ERR_ARG, "%s: more than 2^24 observations", who);
+    const mv::GridLayout layout = mv::make_layout(cfg->grid_x, cfg->grid_y, cfg->grid_z);
+    const mv::LdsPlan plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1, cfg->grid_z);
+    if (plan.bytes == 0)
+        return fail(MV_ERR_CAPACITY, "%s: the occupancy bit rows of one %dx%dx%d grid do not fit in %zu bytes of LDS", who,
+                    cfg->grid_x, cfg->grid_y, cfg->grid_z, mv::kLdsBudget);
+
+    // the pack kernel keeps one whole z layer per wave in LDS
+    if (mv::pack_lds_bytes(layout) + 256 > mv::kLdsBudget)      // + its few static words
+        return fail(MV_ERR_CAPACITY, "%s: one %dx%d layer (x4 waves) does not fit in %zu bytes of LDS while packing", who,
+                    cfg->grid_x, cfg->grid_y, mv::kLdsBudget);
+    *layout_out = layout;
+    *plan_out = plan;
+    return MV_OK;
+}
+
+// Face intensities (flat Lambert shading): every face code has an outward unit normal, and a face is lit by
+// ambient + diffuse * (how far its normal leans towards the light); faces turned away from the light, and
+// the "inside" code, get the ambient term alone.
+static void face_intensities(const mv_config& cfg, float out[mv::kNumFaces])
+{
+    static const signed char kNormal[6][3] = { { -1, 0, 0 }, { 1, 0, 0 }, { 0, -1, 0 }, { 0, 1, 0 }, { 0, 0, -1 }, { 0, 0, 1 } };
+    const double lx = cfg.light_dir[0], ly = cfg.light_dir[1], lz = cfg.light_dir[2];
+    const double ln = std::sqrt(lx * lx + ly * ly + lz * lz);
+    for (int f = 0; f < 6; ++f) {
+        const double lean = ((double)kNormal[f][0] * lx + (double)kNormal[f][1] * ly + (double)kNormal[f][2] * lz) / ln;
+        out[f] = (float)((double)cfg.ambient + (lean > 0.0 ? (double)cfg.diffuse * lean : 0.0));
+    }
+    out[6] = cfg.ambient;
+}
+
+// Launch shape of the render kernel: image tiling, strips of tiles per workgroup, the work list per XCD.
+static int shape_render(mv::RenderParams& p, const mv_config& cfg, const mv::GridLayout& layout, const mv::LdsPlan& plan,
+                        const char* who)
+{
+    const int num_obs = cfg.num_envs * cfg.agents_per_env;
+    p.g = layout;
+    p.voxels_per_env = layout.X * layout.Y * layout.Z;
+    p.threads = plan.threads;
+    p.W = cfg.width; p.H = cfg.height; p.A = cfg.agents_per_env;
+    p.materials_plus_one = (cfg.num_materials + 1);
+    p.tiles_x = (p.W + mv::kTile - 1) / mv::kTile;
+    const int tiles_y = (p.H + mv::kTile - 1) / mv::kTile;
+    p.tiles_per_obs = p.tiles_x * tiles_y;
+    int tpb = cfg.tiles_per_block;
+    int tpb_tail = 0;                                   // 0: no shorter strips at the end of an XCD's work
+    if (tpb <= 0) {
+        // Strips of an observation per workgroup.  Two pulls: (1) enough workgroups to fill 256 CUs a few
+        // times over (about 6144: on 1024 observations of 40x40x16 worlds, 6 strips per observation render
+        // 6 % faster than 8 and 23 % faster than whole observations); (2) when a CU holds four or more
+        // workgroups, so that one workgroup's staging hides behind the others' tracing, three strips per
+        // observation balance the tail best (40x40x16, 128x72: 3 strips of 48 tiles 5 % faster than 2 on
+        // the dynamic workload; 64x64x32 terrain, 256x144, 16 staged layers: 3 strips of 192 tiles 6 %
+        // faster than whole observations or 6 strips).  Grids that leave room for only two workgroups per
+        // CU render whole observations: every strip would re-stage the rows with nothing to hide it.
+        const int waves = p.threads / 64;
+        const long long target_blocks = 256ll * 24;
+        long long strips = (target_blocks + num_obs - 1) / num_obs;
+        if (mv::kLdsBudget / plan.bytes >= 4 && strips < 3) strips = 3;
+        if (strips < 1) strips = 1;
+        tpb = (int)((p.tiles_per_obs + strips - 1) / strips);
+        const int min_tpb = waves * 2;
+        if (tpb < min_tpb) tpb = min_tpb;
+        // The last twentieth (to tenth, see below) of every XCD's observations is cut into strips a third as long: the XCD's
+        // work then ends with short workgroups (4096 x 2 observations, 3 strips of 48 tiles: tail strips of
+        // 16 tiles render 1 % faster than none, strips of 24 or 12 tiles gain less; 1024 x 4 observations:
+        // 3.6 % faster).
+        tpb_tail = tpb / 3;
+        if (tpb_tail < min_tpb) tpb_tail = min_tpb;
+        if (tpb_tail >= tpb) tpb_tail = 0;
+    }
+    if (tpb > p.tiles_per_obs) tpb = p.tiles_per_obs;
+    p.tiles_per_block = tpb;
+    p.blocks_per_obs = (p.tiles_per_obs + tpb - 1) / tpb;
+    p.num_obs = num_obs;
+    p.obs_per_xcd = (num_obs + mv::kXcds - 1) / mv::kXcds;
+    // how much of the range: a twentieth when the launch runs a dozen or more rounds of workgroups through the
+    // chip, up to a tenth when it runs only a few (measured optimum on 1024 and 4096 observations: a tenth)
+    long long per_cu = (long long)(mv::kLdsBudget / plan.bytes);
+    if (per_cu > 32 / (p.threads / 64)) per_cu = 32 / (p.threads / 64);
+    if (per_cu < 1) per_cu = 1;
+    const long long rounds = (long long)p.blocks_per_obs * num_obs / (256 * per_cu);
+    int tail_den = (int)(rounds * 5 / 3);
+    if (tail_den < 10) tail_den = 10;
+    if (tail_den > 20) tail_den = 20;
+    const int tail_obs = tpb_tail > 0 ? p.obs_per_xcd / tail_den : 0;
+    p.obs_body_per_xcd = p.obs_per_xcd - tail_obs;
+    p.tiles_per_block_tail = tail_obs > 0 ? tpb_tail : tpb;
+    p.blocks_per_obs_tail = (p.tiles_per_obs + p.tiles_per_block_tail - 1) / p.tiles_per_block_tail;
+    const unsigned long long per_xcd = (unsigned long long)p.obs_body_per_xcd * (unsigned long long)p.blocks_per_obs +
+                                       (unsigned long long)tail_obs * (unsigned long long)p.blocks_per_obs_tail;
+    if (per_xcd * mv::kXcds > 0x7fffffffull) return fail(MV_ERR_CAPACITY, "%s: too many workgroups", who);
+    p.blocks_per_xcd = (uint32_t)per_xcd;
+    p.sky_packed = (uint32_t)cfg.sky_rgb[0] | ((uint32_t)cfg.sky_rgb[1] << 8) | ((uint32_t)cfg.sky_rgb[2] << 16);
+    p.max_steps = p.g.X + p.g.Y + p.g.Z + 3;
+    return MV_OK;
+}
+
 extern "C" {
 
 const char* mv_last_error(void) { return g_error; }
@@ -122,34 +246,14 @@ void mv_default_config(mv_config* cfg)
 int mv_create_batch(const mv_config* cfg, mv_batch** out)
 {
     if (!cfg || !out) return fail(MV_ERR_ARG, "mv_create_batch: null argument");
-    if (cfg->num_envs <= 0 || cfg->agents_per_env <= 0)
-        return fail(MV_ERR_ARG, "mv_create_batch: num_envs and agents_per_env must be positive");
-    if (cfg->grid_x <= 0 || cfg->grid_y <= 0 || cfg->grid_z <= 0)
-        return fail(MV_ERR_ARG, "mv_create_batch: grid dimensions must be positive");
-    if (cfg->width <= 0 || cfg->height <= 0 || cfg->width > 16384 || cfg->height > 16384)
-        return fail(MV_ERR_ARG, "mv_create_batch: image size must be in 1..16384");
-    if (!(cfg->hfov_rad > 0.0f) || !(cfg->hfov_rad < 3.14159f))
-        return fail(MV_ERR_ARG, "mv_create_batch: hfov_rad must lie in (0, pi)");
-    if (cfg->num_materials < 1 || cfg->num_materials > 255)
-        return fail(MV_ERR_ARG, "mv_create_batch: num_materials must be in 1..255");
-    if (cfg->reserved0 != 0) return fail(MV_ERR_ARG, "mv_create_batch: reserved0 must be 0");
-    if (cfg->tiles_per_block < 0) return fail(MV_ERR_ARG, "mv_create_batch: tiles_per_block must be >= 0");
-    if (cfg->device < 0) return fail(MV_ERR_ARG, "mv_create_batch: device must be >= 0");
-    const double lx = cfg->light_dir[0], ly = cfg->light_dir[1], lz = cfg->light_dir[2];
-    const double ln = std::sqrt(lx * lx + ly * ly + lz * lz);
-    if (!(ln > 0.0) || !std::isfinite(ln)) return fail(MV_ERR_ARG, "mv_create_batch: light_dir must be finite and non-zero");
-    if (!std::isfinite(cfg->ambient) || !std::isfinite(cfg->diffuse))
-        return fail(MV_ERR_ARG, "mv_create_batch: ambient/diffuse must be finite");
-
+    mv::GridLayout layout{};
+    mv::LdsPlan plan{};
+    {
+        const int rc = check_config(cfg, "mv_create_batch", &layout, &plan);
+        if (rc != MV_OK) return rc;
+    }
     const long long voxels = (long long)cfg->grid_x * cfg->grid_y * cfg->grid_z;
-    if (voxels > (1ll << 30)) return fail(MV_ERR_CAPACITY, "mv_create_batch: grid too large");
     const long long num_obs = (long long)cfg->num_envs * cfg->agents_per_env;
-    if (num_obs > (1ll << 24)) return fail(MV_ERR_ARG, "mv_create_batch: more than 2^24 observations");
-    const mv::GridLayout layout = mv::make_layout(cfg->grid_x, cfg->grid_y, cfg->grid_z);
-    const mv::LdsPlan plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1, cfg->grid_z);
-    if (plan.bytes == 0)
-        return fail(MV_ERR_CAPACITY, "mv_create_batch: the occupancy bit rows of one %dx%dx%d grid do not fit in %zu bytes of LDS",
-                    cfg->grid_x, cfg->grid_y, cfg->grid_z, mv::kLdsBudget);
 
     int device_count = 0;
     MV_HIP(hipGetDeviceCount(&device_count));
@@ -167,15 +271,7 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     b->materials_plus_one = cfg->num_materials + 1;
     b->tan_half_x = std::tan(0.5 * (double)cfg->hfov_rad);
     b->tan_half_y = b->tan_half_x * (double)cfg->height / (double)cfg->width;
-    // Face intensities are batch constants (flat Lambert shading): every face code has an outward unit
-    // normal, and a face is lit by ambient + diffuse * (how far its normal leans towards the light); faces
-    // turned away from the light, and the "inside" code, get the ambient term alone.
-    static const signed char kNormal[6][3] = { { -1, 0, 0 }, { 1, 0, 0 }, { 0, -1, 0 }, { 0, 1, 0 }, { 0, 0, -1 }, { 0, 0, 1 } };
-    for (int f = 0; f < 6; ++f) {
-        const double lean = ((double)kNormal[f][0] * lx + (double)kNormal[f][1] * ly + (double)kNormal[f][2] * lz) / ln;
-        b->intensity[f] = (float)((double)cfg->ambient + (lean > 0.0 ? (double)cfg->diffuse * lean : 0.0));
-    }
-    b->intensity[6] = cfg->ambient;
+    face_intensities(*cfg, b->intensity);
     b->env_has_grid.assign((size_t)cfg->num_envs, 0);
     b->env_has_palette.assign((size_t)cfg->num_envs, 0);
 
@@ -205,7 +301,7 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     }
     if (e == hipSuccess) e = mv::launch_pixel_scalars(b->d_sx, b->d_sy, cfg->width, cfg->height, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
-    if (e == hipSuccess) e = mv::prepare_render(plan.bytes);
+    if (e == hipSuccess) e = mv::prepare_kernels();
     if (e != hipSuccess) {
         free_batch(b);
         return fail(MV_ERR_HIP, "mv_create_batch: device set-up failed: %s", hipGetErrorString(e));
@@ -371,65 +467,10 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.active = b->all_active ? nullptr : b->d_active;
     p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
     p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
-    p.g = b->layout;
-    p.voxels_per_env = b->voxels_per_env;
-    p.threads = plan.threads;
-    p.W = b->cfg.width; p.H = b->cfg.height; p.A = b->cfg.agents_per_env;
-    p.materials_plus_one = b->materials_plus_one;
-    p.tiles_x = (p.W + mv::kTile - 1) / mv::kTile;
-    const int tiles_y = (p.H + mv::kTile - 1) / mv::kTile;
-    p.tiles_per_obs = p.tiles_x * tiles_y;
-    int tpb = b->cfg.tiles_per_block;
-    int tpb_tail = 0;                                   // 0: no shorter strips at the end of an XCD's work
-    if (tpb <= 0) {
-        // Strips of an observation per workgroup.  Two pulls: (1) enough workgroups to fill 256 CUs a few
-        // times over (about 6144: on 1024 observations of 40x40x16 worlds, 6 strips per observation render
-        // 6 % faster than 8 and 23 % faster than whole observations); (2) when a CU holds four or more
-        // workgroups, so that one workgroup's staging hides behind the others' tracing, three strips per
-        // observation balance the tail best (40x40x16, 128x72: 3 strips of 48 tiles 5 % faster than 2 on
-        // the dynamic workload; 64x64x32 terrain, 256x144, 16 staged layers: 3 strips of 192 tiles 6 %
-        // faster than whole observations or 6 strips).  Grids that leave room for only two workgroups per
-        // CU render whole observations: every strip would re-stage the rows with nothing to hide it.
-        const int waves = p.threads / 64;
-        const long long target_blocks = 256ll * 24;
-        long long strips = (target_blocks + b->num_obs - 1) / b->num_obs;
-        if (mv::kLdsBudget / plan.bytes >= 4 && strips < 3) strips = 3;
-        if (strips < 1) strips = 1;
-        tpb = (int)((p.tiles_per_obs + strips - 1) / strips);
-        const int min_tpb = waves * 2;
-        if (tpb < min_tpb) tpb = min_tpb;
-        // The last twentieth (to tenth, see below) of every XCD's observations is cut into strips a third as long: the XCD's
-        // work then ends with short workgroups (4096 x 2 observations, 3 strips of 48 tiles: tail strips of
-        // 16 tiles render 1 % faster than none, strips of 24 or 12 tiles gain less; 1024 x 4 observations:
-        // 3.6 % faster).
-        tpb_tail = tpb / 3;
-        if (tpb_tail < min_tpb) tpb_tail = min_tpb;
-        if (tpb_tail >= tpb) tpb_tail = 0;
+    {
+        const int rc = shape_render(p, b->cfg, b->layout, plan, "mv_render_batch");
+        if (rc != MV_OK) return rc;
     }
-    if (tpb > p.tiles_per_obs) tpb = p.tiles_per_obs;
-    p.tiles_per_block = tpb;
-    p.blocks_per_obs = (p.tiles_per_obs + tpb - 1) / tpb;
-    p.num_obs = b->num_obs;
-    p.obs_per_xcd = (b->num_obs + mv::kXcds - 1) / mv::kXcds;
-    // how much of the range: a twentieth when the launch runs a dozen or more rounds of workgroups through the
-    // chip, up to a tenth when it runs only a few (measured optimum on 1024 and 4096 observations: a tenth)
-    long long per_cu = (long long)(mv::kLdsBudget / plan.bytes);
-    if (per_cu > 32 / (p.threads / 64)) per_cu = 32 / (p.threads / 64);
-    if (per_cu < 1) per_cu = 1;
-    const long long rounds = (long long)p.blocks_per_obs * b->num_obs / (256 * per_cu);
-    int tail_den = (int)(rounds * 5 / 3);
-    if (tail_den < 10) tail_den = 10;
-    if (tail_den > 20) tail_den = 20;
-    const int tail_obs = tpb_tail > 0 ? p.obs_per_xcd / tail_den : 0;
-    p.obs_body_per_xcd = p.obs_per_xcd - tail_obs;
-    p.tiles_per_block_tail = tail_obs > 0 ? tpb_tail : tpb;
-    p.blocks_per_obs_tail = (p.tiles_per_obs + p.tiles_per_block_tail - 1) / p.tiles_per_block_tail;
-    const unsigned long long per_xcd = (unsigned long long)p.obs_body_per_xcd * (unsigned long long)p.blocks_per_obs +
-                                       (unsigned long long)tail_obs * (unsigned long long)p.blocks_per_obs_tail;
-    if (per_xcd * mv::kXcds > 0x7fffffffull) return fail(MV_ERR_CAPACITY, "mv_render_batch: too many workgroups");
-    p.blocks_per_xcd = (uint32_t)per_xcd;
-    p.sky_packed = (uint32_t)b->cfg.sky_rgb[0] | ((uint32_t)b->cfg.sky_rgb[1] << 8) | ((uint32_t)b->cfg.sky_rgb[2] << 16);
-    p.max_steps = p.g.X + p.g.Y + p.g.Z + 3;
     MV_HIP(mv::launch_render(p, plan.bytes, (hipStream_t)hip_stream));
     return MV_OK;
 }

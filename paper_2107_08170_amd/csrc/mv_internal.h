@@ -107,7 +107,10 @@ hipError_t launch_bars(uint8_t* rgb, const float* fraction, const uint8_t* activ
                        const BarParams& bar, hipStream_t stream);
 // active[i] = (done[i] == 0) for the n environments of a batch
 hipError_t launch_active_from_done(const uint8_t* done, uint8_t* active, int n, hipStream_t stream);
-hipError_t prepare_render(size_t lds_bytes);
+// raises the dynamic-LDS limit of the render and pack kernels on the current device (cheap after the first call)
+hipError_t prepare_kernels();
+// dynamic LDS the pack kernel asks for: one z layer per wave
+size_t pack_lds_bytes(const GridLayout& g);
 hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t stream);
 
 }  // namespace mv

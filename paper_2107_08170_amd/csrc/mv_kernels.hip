@@ -14,6 +14,7 @@
 #include "mv_internal.h"
 
 #include <math.h>
+#include <atomic>
 #include <type_traits>
 
 namespace mv {
@@ -362,6 +363,12 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
     }
 }
 
+size_t pack_lds_bytes(const GridLayout& g)
+{
+    const size_t XY = (size_t)g.X * g.Y;
+    return ((XY + 15) & ~(size_t)15) * (kPackThreads / 64);
+}
+
 hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst, int32_t* ztop_dst, int count,
                        const GridLayout& g, const uint8_t* pal_src, uint8_t* pal_dst, uint32_t* lut_dst,
                        int materials_plus_one, const float intensity[kNumFaces], const HeightFeedback& heights,
@@ -370,8 +377,7 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
     Intensities I;
     for (int f = 0; f < kNumFaces; ++f) I.v[f] = intensity[f];
     const size_t XY = (size_t)g.X * g.Y;
-    const size_t layer_stride = (XY + 15) & ~(size_t)15;
-    const size_t lds = layer_stride * (kPackThreads / 64);
+    const size_t lds = pack_lds_bytes(g);
     // 0: byte access; 1: dword access; 2: 16-byte access to the layers (sizes and both pointers aligned)
     int vec_ok = (XY % 4 == 0) && ((reinterpret_cast<uintptr_t>(src) & 3) == 0) &&
                  ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
@@ -1160,20 +1166,35 @@ hipError_t launch_active_from_done(const uint8_t* done, uint8_t* active, int n, 
 }
 
 template <bool AUX, bool PACKED, bool FAST>
-static hipError_t set_lds_limit(size_t lds_bytes)
+static hipError_t set_lds_limit()
 {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<AUX, PACKED, FAST>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
 }
 
-hipError_t prepare_render(size_t lds_bytes)
+// Workgroups of the render and pack kernels may ask for more dynamic LDS than the default limit: raise the limit
+// of every instantiation to the whole LDS of a compute unit, once per device (the attribute belongs to the
+// function on the current device, not to a batch: a value derived from one batch's plan would be wrong for
+// the next batch).
+hipError_t prepare_kernels()
 {
-    if (lds_bytes <= 48 * 1024) return hipSuccess;
-    hipError_t e = hipSuccess;
-#define MV_SET(A, P, F) if (e == hipSuccess) e = set_lds_limit<A, P, F>(lds_bytes)
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> done[kMaxDevices];
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device >= 0 && device < kMaxDevices && done[device].load(std::memory_order_acquire)) return hipSuccess;
+#define MV_SET(A, P, F) if (e == hipSuccess) e = set_lds_limit<A, P, F>()
     MV_SET(false, false, false); MV_SET(false, false, true); MV_SET(false, true, false); MV_SET(false, true, true);
     MV_SET(true, false, false);  MV_SET(true, false, true);  MV_SET(true, true, false);  MV_SET(true, true, true);
 #undef MV_SET
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_kernel<8>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kLdsBudget);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_kernel<16>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kLdsBudget);
+    if (e == hipSuccess && device >= 0 && device < kMaxDevices) done[device].store(true, std::memory_order_release);
     return e;
 }
 

@@ -85,6 +85,18 @@ def test_create_rejects_zero_light_and_oversized_grid(lib):
     assert b"LDS" in lib.mv_last_error()
 
 
+def test_create_rejects_layers_the_pack_kernel_cannot_hold(lib):
+    """256x256x2: only 16 KiB of occupancy bits (fits the render plan), but the pack kernel keeps a whole 64 KiB
+    layer per wave in LDS, four waves: beyond a compute unit's 160 KiB.  Must be refused at creation, not fail at
+    the first upload."""
+    cfg = binding.default_config()
+    cfg.num_envs, cfg.agents_per_env, cfg.num_materials = 1, 1, 4
+    cfg.grid_x, cfg.grid_y, cfg.grid_z = 256, 256, 2
+    handle = C.c_void_p()
+    assert lib.mv_create_batch(C.byref(cfg), C.byref(handle)) == binding.MV_ERR_CAPACITY
+    assert b"packing" in lib.mv_last_error() and handle.value is None
+
+
 def test_null_arguments(lib):
     handle = C.c_void_p()
     assert lib.mv_create_batch(None, C.byref(handle)) == binding.MV_ERR_ARG
