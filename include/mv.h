@@ -225,6 +225,31 @@ void mv_host_free(void* ptr);
 int mv_fetch_observations(mv_batch* batch, const uint8_t* rgb_dev, const float* depth_dev, int32_t first_obs,
                           int32_t count, uint8_t* rgb_host, float* depth_host, void* hip_stream);
 
+/* The whole path in one call for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Equivalent to mv_create_batch(cfg) + mv_upload_worlds +
+ * mv_set_cameras + mv_render_batch (no aux outputs) on device inputs, but without a batch object: the working
+ * memory a batch would own (occupancy bit rows, top layers, colour tables, camera records, pixel scalars) is a
+ * fixed array of MV_NOALLOC_SCRATCH_BYTES inside the library's device image, one copy per GPU, held until the
+ * process ends.  The call allocates nothing (no hipMalloc, hipFree or host heap), copies nothing to the host
+ * and does not wait.
+ *   voxels     : device [N, Z, Y, X] uint8 material ids; read by the kernels of this call, not copied: keep it
+ *                unchanged until the stream has passed the call.  Not validated (ids above num_materials are
+ *                clamped when shading).
+ *   palette    : device [N, num_materials+1, 3] uint8, required.
+ *   cams       : device [N*A, 5] float32 (x, y, z, yaw, pitch); self_voxel : device [N*A] int32 or NULL.
+ *   rgb, depth : device outputs as for mv_render_batch.
+ * Working memory needed: N * (8 * (Z*Y*ceil(X/64) + Z*X*ceil(Y/64)) + 28 * (num_materials+1) + 4) + 64 * N*A +
+ * 4 * (W + H) bytes plus up to 256 bytes of padding per piece; a configuration that needs more than
+ * MV_NOALLOC_SCRATCH_BYTES is refused with MV_ERR_CAPACITY before anything is enqueued (256 environments x 4
+ * agents of 40x40x16 voxels need 2.8 MB).  Every call on a GPU uses that GPU's one array: calls that overlap
+ * on one GPU (two streams, two threads) race; order them.  Each call rewrites every word it later reads, so
+ * what an earlier call left behind never shows.  cfg->tiles_per_block is honoured as in mv_create_batch.
+ * Errors: MV_ERR_ARG, MV_ERR_CAPACITY, MV_ERR_HIP. */
+#define MV_NOALLOC_SCRATCH_BYTES (8u << 20)
+int mv_render_worlds_noalloc(const mv_config* cfg, const uint8_t* voxels, const uint8_t* palette,
+                             const float* cams, const int32_t* self_voxel, uint8_t* rgb, float* depth,
+                             void* hip_stream);
+
 /* Free the batch and its device memory (synchronises the device first).  NULL is a no-op. */
 void mv_destroy(mv_batch* batch);
 

@@ -1,4 +1,4 @@
-"""ctypes binding of ``libmv.so``: the same five calls as ``include/mv.h``, argument marshalling only.
+"""ctypes binding of ``libmv.so``: the same calls as ``include/mv.h``, argument marshalling only.
 
 Every step of the render path runs in the HIP kernels behind the C ABI; there is no Python or CPU
 fallback.  If the library has not been built, loading fails with an error that says how to build
@@ -20,7 +20,8 @@ FACE_INSIDE, FACE_MISS = 6, 255
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
            "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_step", "mv_host_alloc", "mv_host_free",
            "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records",
-           "mv_debug_set_staged_layers")
+           "mv_debug_set_staged_layers", "mv_render_worlds_noalloc")
+NOALLOC_SCRATCH_BYTES = 8 << 20
 
 
 class MvConfig(C.Structure):
@@ -86,6 +87,7 @@ def load_library():
                                        C.POINTER(C.c_int32), C.POINTER(vp)]
     lib.mv_debug_camera_records.argtypes = [vp, C.POINTER(vp)]
     lib.mv_debug_set_staged_layers.argtypes = [vp, C.c_int32]
+    lib.mv_render_worlds_noalloc.argtypes = [C.POINTER(MvConfig), vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -118,6 +120,39 @@ def _is_device(x) -> bool:
     return bool(getattr(x, "is_cuda", False))
 
 
+def make_config(num_envs: int, agents_per_env: int, grid: Sequence[int], num_materials: int,
+                width: int = 128, height: int = 72, hfov_rad: Optional[float] = None,
+                light_dir: Optional[Sequence[float]] = None, ambient: Optional[float] = None,
+                diffuse: Optional[float] = None, sky_rgb: Optional[Sequence[int]] = None,
+                device: int = 0, tiles_per_block: int = 0) -> MvConfig:
+    """``mv_default_config`` with the given fields filled in."""
+    cfg = default_config()
+    cfg.num_envs, cfg.agents_per_env = num_envs, agents_per_env
+    cfg.grid_x, cfg.grid_y, cfg.grid_z = (int(g) for g in grid)
+    cfg.width, cfg.height = width, height
+    cfg.num_materials = num_materials
+    if hfov_rad is not None:
+        cfg.hfov_rad = hfov_rad
+    if light_dir is not None:
+        cfg.light_dir[:] = [float(v) for v in light_dir]
+    if ambient is not None:
+        cfg.ambient = ambient
+    if diffuse is not None:
+        cfg.diffuse = diffuse
+    if sky_rgb is not None:
+        cfg.sky_rgb[:] = [int(v) for v in sky_rgb]
+    cfg.device = device
+    cfg.tiles_per_block = tiles_per_block
+    return cfg
+
+
+def render_worlds_noalloc(cfg: MvConfig, voxels, palette, cams, self_voxel, rgb, depth, stream: int = 0) -> None:
+    """``mv_render_worlds_noalloc``: pack, cameras and render in one call that allocates nothing; all array
+    arguments are device tensors (or raw device addresses)."""
+    _check(load_library().mv_render_worlds_noalloc(C.byref(cfg), _as_ptr(voxels), _as_ptr(palette), _as_ptr(cams),
+                                                   _as_ptr(self_voxel), _as_ptr(rgb), _as_ptr(depth), stream))
+
+
 class PinnedBuffer:
     """Page-locked host memory from ``mv_host_alloc``; ``array(dtype, shape)`` views it as a NumPy array."""
 
@@ -146,23 +181,8 @@ class Batch:
                  diffuse: Optional[float] = None, sky_rgb: Optional[Sequence[int]] = None,
                  device: int = 0, tiles_per_block: int = 0):
         lib = load_library()
-        cfg = default_config()
-        cfg.num_envs, cfg.agents_per_env = num_envs, agents_per_env
-        cfg.grid_x, cfg.grid_y, cfg.grid_z = (int(g) for g in grid)
-        cfg.width, cfg.height = width, height
-        cfg.num_materials = num_materials
-        if hfov_rad is not None:
-            cfg.hfov_rad = hfov_rad
-        if light_dir is not None:
-            cfg.light_dir[:] = [float(v) for v in light_dir]
-        if ambient is not None:
-            cfg.ambient = ambient
-        if diffuse is not None:
-            cfg.diffuse = diffuse
-        if sky_rgb is not None:
-            cfg.sky_rgb[:] = [int(v) for v in sky_rgb]
-        cfg.device = device
-        cfg.tiles_per_block = tiles_per_block
+        cfg = make_config(num_envs, agents_per_env, grid, num_materials, width, height, hfov_rad, light_dir, ambient,
+                          diffuse, sky_rgb, device, tiles_per_block)
         self.cfg = cfg
         self._h = C.c_void_p()
         _check(lib.mv_create_batch(C.byref(cfg), C.byref(self._h)))

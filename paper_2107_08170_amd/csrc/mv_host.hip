@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -136,7 +137,7 @@ static int check_config(const mv_config* cfg, const char* who, mv::GridLayout* l
                     cfg->grid_x, cfg->grid_y, cfg->grid_z, mv::kLdsBudget);
 
     // the pack kernel keeps one whole z layer per wave in LDS
-    if (mv::pack_lds_bytes(layout) + 256 > mv::kLdsBudget)      // + its few static words
+    if (mv::pack_lds_bytes(layout) + mv::kPackStaticLds > mv::kLdsBudget)
         return fail(MV_ERR_CAPACITY, "%s: one %dx%d layer (x4 waves) does not fit in %zu bytes of LDS while packing", who,
                     cfg->grid_x, cfg->grid_y, mv::kLdsBudget);
     *layout_out = layout;
@@ -621,3 +622,123 @@ int mv_debug_camera_records(mv_batch* b, const void** records)
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// mv_render_worlds_noalloc: the whole path for callers that must not allocate.  What a batch object keeps in
+// memory from mv_create_batch (bit rows, top layers, colour tables, camera records, pixel scalars) lives in one
+// file-scope device array instead; every GPU the library runs on holds its own copy of it until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the device address is looked
+// up once per device and only that address is ever passed to a kernel.
+// ------------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kScratchBytes = MV_NOALLOC_SCRATCH_BYTES;
+constexpr int kScratchDevices = 64;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kScratchDevices] = {};
+
+// device address of this device's copy of `scratch` (the device must be current)
+int scratch_address(int device, unsigned char** out)
+{
+    if (device < 0 || device >= kScratchDevices)
+        return fail(MV_ERR_ARG, "mv_render_worlds_noalloc: device %d outside 0..%d", device, kScratchDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        MV_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(MV_ERR_HIP, "mv_render_worlds_noalloc: no device address for the scratch array");
+        g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return MV_OK;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" int mv_render_worlds_noalloc(const mv_config* cfg, const uint8_t* voxels, const uint8_t* palette,
+                                        const float* cams, const int32_t* self_voxel, uint8_t* rgb, float* depth,
+                                        void* hip_stream)
+{
+    if (!cfg || !voxels || !palette || !cams || !rgb || !depth)
+        return fail(MV_ERR_ARG, "mv_render_worlds_noalloc: null argument");
+    if (reinterpret_cast<uintptr_t>(depth) & 3)
+        return fail(MV_ERR_ARG, "mv_render_worlds_noalloc: depth must be 4-byte aligned");
+    mv::GridLayout layout{};
+    mv::LdsPlan plan{};
+    {
+        const int rc = check_config(cfg, "mv_render_worlds_noalloc", &layout, &plan);
+        if (rc != MV_OK) return rc;
+    }
+    const size_t N = (size_t)cfg->num_envs, NA = N * (size_t)cfg->agents_per_env;
+    const int mp1 = cfg->num_materials + 1;
+    // carve the scratch array: [bit rows][colour tables][top layers][camera records][sx][sy]
+    size_t off = 0;
+    const size_t off_bits = off;  off = align256(off + N * (size_t)layout.env_words * 8);
+    const size_t off_lut = off;   off = align256(off + N * (size_t)mv::kNumFaces * mp1 * 4);
+    const size_t off_ztop = off;  off = align256(off + N * 4);
+    const size_t off_rec = off;   off = align256(off + NA * sizeof(mv::CameraRecord));
+    const size_t off_sx = off;    off = align256(off + (size_t)cfg->width * 4);
+    const size_t off_sy = off;    off = align256(off + (size_t)cfg->height * 4);
+    if (off > kScratchBytes)
+        return fail(MV_ERR_CAPACITY, "mv_render_worlds_noalloc: %d environments x %d agents of %dx%dx%d voxels need %zu bytes "
+                    "of working memory, the fixed scratch array holds %zu; use a batch object (mv_create_batch) instead",
+                    cfg->num_envs, cfg->agents_per_env, cfg->grid_x, cfg->grid_y, cfg->grid_z, off, kScratchBytes);
+
+    int device_count = 0;
+    MV_HIP(hipGetDeviceCount(&device_count));
+    if (cfg->device >= device_count)
+        return fail(MV_ERR_ARG, "mv_render_worlds_noalloc: device %d of %d", cfg->device, device_count);
+    DeviceScope scope(cfg->device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_render_worlds_noalloc: cannot select device %d", cfg->device);
+    unsigned char* base = nullptr;
+    {
+        const int rc = scratch_address(cfg->device, &base);
+        if (rc != MV_OK) return rc;
+    }
+    MV_HIP(mv::prepare_kernels());
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint64_t* d_bits = reinterpret_cast<uint64_t*>(base + off_bits);
+    uint32_t* d_lut = reinterpret_cast<uint32_t*>(base + off_lut);
+    int32_t* d_ztop = reinterpret_cast<int32_t*>(base + off_ztop);
+    mv::CameraRecord* d_rec = reinterpret_cast<mv::CameraRecord*>(base + off_rec);
+    float* d_sx = reinterpret_cast<float*>(base + off_sx);
+    float* d_sy = reinterpret_cast<float*>(base + off_sy);
+
+    float intensity[mv::kNumFaces];
+    face_intensities(*cfg, intensity);
+    const double tan_half_x = std::tan(0.5 * (double)cfg->hfov_rad);
+    const double tan_half_y = tan_half_x * (double)cfg->height / (double)cfg->width;
+    const mv::HeightFeedback no_feedback{ nullptr, nullptr };
+
+    // Every word of the scratch regions used below is rewritten by these launches before the render reads it
+    // (pack writes every row word, top layer and table entry of every environment), so nothing left over from an
+    // earlier, larger call can show through and nothing needs clearing.
+    MV_HIP(mv::launch_pixel_scalars(d_sx, d_sy, cfg->width, cfg->height, stream));
+    // source and destination of the material and palette copies are the caller's own arrays: nothing is copied,
+    // the render reads the material of a hit voxel from `voxels` directly
+    MV_HIP(mv::launch_pack(voxels, const_cast<uint8_t*>(voxels), d_bits, d_ztop, cfg->num_envs, layout, palette,
+                           const_cast<uint8_t*>(palette), d_lut, mp1, intensity, no_feedback, stream));
+    MV_HIP(mv::launch_cameras(cams, self_voxel, d_rec, (int)NA, tan_half_x, tan_half_y, cfg->grid_x * cfg->grid_y, stream));
+
+    mv::RenderParams p{};
+    p.staged_layers = cfg->grid_z;            // no height feedback without a batch object: stage every layer
+    p.heights = no_feedback;
+    p.active = nullptr;
+    p.bits = d_bits; p.ztop = d_ztop; p.vox = voxels; p.lut = d_lut; p.rec = d_rec; p.sx = d_sx; p.sy = d_sy;
+    p.rgb = rgb; p.depth = depth;
+    {
+        const int rc = shape_render(p, *cfg, layout, plan, "mv_render_worlds_noalloc");
+        if (rc != MV_OK) return rc;
+    }
+    MV_HIP(mv::launch_render(p, plan.bytes, stream));
+    return MV_OK;
+}

@@ -20,6 +20,7 @@ constexpr int kTile = 8;                  // a wave renders an 8x8 pixel tile
 constexpr int kXcds = 8;                  // MI355X: 8 XCDs, workgroups are dealt round-robin
 constexpr int kNumFaces = 7;              // six faces + "inside"
 constexpr size_t kLdsBudget = 160 * 1024; // LDS one workgroup may use on gfx950
+constexpr size_t kPackStaticLds = 1024;   // room kept for the pack kernel's static LDS words next to its dynamic share
 
 // Occupancy bits in device memory, per environment ("bit rows"):
 //   x rows: Z*Y rows of rowwords_x 64-bit words; row (k*Y + j), bit i   <-> voxel (i,j,k)

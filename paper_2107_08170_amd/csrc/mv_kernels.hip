@@ -1188,12 +1188,14 @@ hipError_t prepare_kernels()
     MV_SET(false, false, false); MV_SET(false, false, true); MV_SET(false, true, false); MV_SET(false, true, true);
     MV_SET(true, false, false);  MV_SET(true, false, true);  MV_SET(true, true, false);  MV_SET(true, true, true);
 #undef MV_SET
+    // the pack kernel also has a few static words of LDS: its dynamic share must leave room for them
+    const int pack_limit = (int)(kLdsBudget - kPackStaticLds);
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_kernel<8>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kLdsBudget);
+                                pack_limit);
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_kernel<16>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kLdsBudget);
+                                pack_limit);
     if (e == hipSuccess && device >= 0 && device < kMaxDevices) done[device].store(true, std::memory_order_release);
     return e;
 }
