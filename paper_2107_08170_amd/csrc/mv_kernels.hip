@@ -36,10 +36,11 @@ GridLayout make_layout(int X, int Y, int Z)
 }
 
 constexpr int kScanClasses = 16;        // (dominant axis) x (direction along u, v, z)
+constexpr int kClassStride = 128;       // bytes between scan-class records in LDS (80 used): a ray's record offset is a shift
 
 static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
-// LDS map (bytes):  [16 scan-class records, 80 B each] | [sx: W floats][sy: H floats] |
+// LDS map (bytes):  [16 scan-class records, 128 B apart] | [sx: W floats][sy: H floats] |
 //                   [colour table 7*(M+1) dwords] | bit rows
 // fast grids stage four row arrays (x, x mirrored, y, y mirrored) of `staged_layers` layers each; others stage
 // all x rows.
@@ -52,7 +53,7 @@ static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one,
 {
     LdsMap m{};
     size_t off = 0;
-    m.classes = (uint32_t)off; off += kScanClasses * 80;
+    m.classes = (uint32_t)off; off += kScanClasses * kClassStride;
     m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
     m.lut = (uint32_t)off;
     off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
@@ -646,14 +647,6 @@ __device__ __forceinline__ int ctz64_nonzero(uint64_t v)
     return (int)min(flo, 32u + fhi);
 }
 
-// all ones if the sign bit of x is set, zero otherwise (kept opaque so that "mask & constant" stays one AND)
-__device__ __forceinline__ uint32_t sign_mask(float x)
-{
-    uint32_t m;
-    asm("v_ashrrev_i32 %0, 31, %1" : "=v"(m) : "v"(x));
-    return m;
-}
-
 // v & 1 as a 32-bit operation of its own (the compiler otherwise widens the test back to the 64-bit row)
 __device__ __forceinline__ uint32_t low_bit(uint32_t v)
 {
@@ -696,11 +689,15 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
     const float dv = xm ? dy : dx;
-    // class record at 80*class from the start of the workgroup's dynamic LDS.  Along v and z a component
+    // class = 8*(y dominant) + 4*(u negative) + 2*(v negative) + (z negative): each funnel shift moves the
+    // index up one bit and brings in the sign bit of the next component.  Along v and z a component
     // of -0 counts as positive (the ray never crosses a plane of that axis, and the distance to the
     // upper plane is never 0 inside the cell): adding +0 turns -0 into +0 and changes nothing else.
-    const uint32_t qoff = (xm ? 0u : 640u) + (sign_mask(du) & 320u) + (sign_mask(dv + 0.0f) & 160u) +
-                          (sign_mask(dz + 0.0f) & 80u);
+    uint32_t q = xm ? 0u : 1u;
+    q = __builtin_amdgcn_alignbit(q, __float_as_uint(du), 31);
+    q = __builtin_amdgcn_alignbit(q, __float_as_uint(dv + 0.0f), 31);
+    q = __builtin_amdgcn_alignbit(q, __float_as_uint(dz + 0.0f), 31);
+    const uint32_t qoff = q * (uint32_t)kClassStride;
     ScanClass c;
     {
         lds_u32x4_ptr rec = (lds_u32x4_ptr)(uintptr_t)(classes_addr + qoff);
@@ -710,47 +707,122 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 
     const float dua = fabsf(du);
     const float inv_u = safe_rcp(dua);
-    const float dt_v = fabsf(safe_rcp(dv)), dt_z = fabsf(safe_rcp(dz));
+    const float rcp_v = safe_rcp(dv), rcp_z = safe_rcp(dz);
+    const float dt_v = fabsf(rcp_v), dt_z = fabsf(rcp_z);
     // first crossing on an axis: the distance to the first plane in the ray's direction times |1/d|
     const float t0_v = c.dist_v * dt_v;
     const float t0_z = c.dist_z * dt_z;
     // leaving the grid: same n*dt + t0 expression as the crossings, so the comparison below is exact
     const float t_end = vmin3(c.uexit * inv_u, fmaf(c.nv_max, dt_v, t0_v), fmaf(c.nz_max, dt_z, t0_z));
 
-    float t_v = t0_v, t_z = t0_z, n_v = 0.0f, n_z = 0.0f;
+    // crossings made so far along v and z (without sign; the directions sit in the class), and the parameters
+    // of the next ones: t_v = n_v*dt_v + t0_v, t_z likewise
+    float t_v, t_z, n_v = 0.0f, n_z = 0.0f;
     uint32_t addr = (uint32_t)c.addr0;
     uint64_t r, in_range;
     int i_last;
     // One turn of the loop scans the current row from cell i_from up to the cell i_to where the ray leaves
-    // it.  The second shift count is 63 - (i_to - i_from) = (i_from + ~i_to) mod 64: one xor-add, the
+    // it (parameter t_out = min(t_v, t_z), for narrow grids also capped at t_end): r = row >> i_from,
+    // in_range = r << (63 - (i_to - i_from)), non-zero if a solid cell lies in the run; the loop ends there, or
+    // when t_out reaches t_end (the ray leaves the grid); otherwise the ray crosses the nearer of the two planes
+    // (v first at a tie), the counter of that axis and the row address step, and the crossing parameters are
+    // recomputed.  The second shift count is 63 - (i_to - i_from) = (i_from + ~i_to) mod 64: one xor-add, the
     // shifter ignores the upper bits.  Nothing after the loop needs i_from: the hit cell follows from
     // the lowest set bit of in_range and i_to, and bit 0 of r tells whether it is the row's entry cell.
     // The next row is requested as soon as its address is known, at the end of the turn before (render -1 %).
     uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;
-#define MV_ROW_TURN(i_from, i_to)                                                             \
-    {                                                                                         \
-        const float t_out = kNarrow ? vmin3(t_v, t_z, t_end) : vmin(t_v, t_z);                \
-        const float u_out = fmaf(t_out, dua, c.Pu);                                           \
-        i_to = kNarrow ? (int)u_out : min((int)u_out, c.um1);                                 \
-        r = row >> (i_from);                                                                  \
-        in_range = r << ((((i_to) ^ -1) + (i_from)) & 63);                                    \
-        i_last = i_to;                                                                        \
-        if ((in_range != 0) | !(t_out < t_end)) break;                                        \
-        const bool cv = t_v <= t_z;                                                           \
-        const float one_v = cv ? 1.0f : 0.0f;                                                 \
-        n_v += one_v;                                                                         \
-        n_z += 1.0f - one_v;                                                                  \
-        addr += (uint32_t)(cv ? c.sv : c.sz);                                                 \
-        row = *(lds_u64_ptr)(uintptr_t)addr;                                                  \
-        t_v = fmaf(n_v, dt_v, t0_v);                                                          \
-        t_z = fmaf(n_z, dt_z, t0_z);                                                          \
-    }
     int i_a = c.i0, i_b;
-    for (;;) {                                  // two turns per trip: the cell index alternates registers
-        MV_ROW_TURN(i_a, i_b)
-        MV_ROW_TURN(i_b, i_a)
+    // The loop in assembly: the compiler's structured control flow spends about ten scalar instructions per turn
+    // on lane masks (two breaks per trip); written out, a turn needs two.  Lanes that are done simply leave
+    // the execution mask (it only ever shrinks; restored after the loop), so every register of a finished lane
+    // keeps the values of its last turn.  The cell index alternates between i_a and i_b from turn to turn; a
+    // turn that writes i_a copies it to i_b, so that i_b holds the last cell of a lane whichever turn it left in.
+    // The first turn is peeled: it reads the first crossings straight from t0_v / t0_z and starts the crossing
+    // counters instead of incrementing them.  The v-or-z decision of a turn is taken at its top (VCC), well ahead
+    // of the selects that read it (a vector instruction may not read a lane mask within two instructions of the
+    // one that wrote it).
+    {
+        uint64_t exec_save, m_go, m_empty;
+        float t_out, tmp;
+        int sh;
+        // the run of cells [IFROM, ITO] of the current row: ITO from the parameter at which the ray leaves the row
+        // (TOUT, NARROW: capped at the grid exit; else the cell is clamped to U - 1), then the two shifts
+#define MV_ASM_TEST(TV, TZ, IFROM, ITO, TOUT_AND_CELL)                                  \
+            "v_cmp_le_f32_e32 vcc, " TV ", " TZ "\n\t"                                   \
+            TOUT_AND_CELL(TV, TZ, ITO)                                                   \
+            "v_cmp_lt_f32_e64 %[mgo], %[tout], %[tend]\n\t"                             \
+            "s_waitcnt lgkmcnt(0)\n\t"                                                  \
+            "v_lshrrev_b64 %[r], " IFROM ", %[row]\n\t"                                 \
+            "v_xad_u32 %[sh], " ITO ", -1, " IFROM "\n\t"                               \
+            "v_lshlrev_b64 %[inr], %[sh], %[r]\n\t"                                     \
+            "v_cmp_eq_u64_e64 %[mempty], 0, %[inr]\n\t"
+#define MV_ASM_CELL_NARROW(TV, TZ, ITO)                                                 \
+            "v_min3_f32 %[tout], " TV ", " TZ ", %[tend]\n\t"                            \
+            "v_fma_f32 %[tmp], %[tout], |%[du]|, %[pu]\n\t"                             \
+            "v_cvt_i32_f32_e32 " ITO ", %[tmp]\n\t"
+#define MV_ASM_CELL_WIDE(TV, TZ, ITO)                                                   \
+            "v_min_f32_e32 %[tout], " TV ", " TZ "\n\t"                                  \
+            "v_fma_f32 %[tmp], %[tout], |%[du]|, %[pu]\n\t"                             \
+            "v_cvt_i32_f32_e32 %[tmp], %[tmp]\n\t"                                      \
+            "v_min_i32_e32 " ITO ", %[tmp], %[um1]\n\t"
+#define MV_ASM_LEAVE                                                                    \
+            "s_and_b64 exec, %[mgo], %[mempty]\n\t"                                     \
+            "s_cbranch_execz 2f\n\t"
+#define MV_ASM_NEXT_ROW                                                                 \
+            "v_cndmask_b32_e32 %[tmp], %[sz], %[sv], vcc\n\t"                           \
+            "v_add_u32_e32 %[addr], %[addr], %[tmp]\n\t"                                \
+            "ds_read_b64 %[row], %[addr]\n\t"
+#define MV_ASM_FIRST_ADVANCE                                                            \
+            MV_ASM_NEXT_ROW                                                             \
+            "v_cndmask_b32_e64 %[nv], 0, 1.0, vcc\n\t"                                  \
+            "v_sub_f32_e32 %[nz], 1.0, %[nv]\n\t"                                       \
+            "v_fma_f32 %[tv], %[nv], |%[rv]|, %[t0v]\n\t"                               \
+            "v_fma_f32 %[tz], %[nz], |%[rz]|, %[t0z]\n\t"
+#define MV_ASM_ADVANCE                                                                  \
+            MV_ASM_NEXT_ROW                                                             \
+            "v_cndmask_b32_e64 %[tmp], 0, 1.0, vcc\n\t"                                 \
+            "v_add_f32_e32 %[nv], %[nv], %[tmp]\n\t"                                    \
+            "v_sub_f32_e32 %[tmp], 1.0, %[tmp]\n\t"                                     \
+            "v_add_f32_e32 %[nz], %[nz], %[tmp]\n\t"                                    \
+            "v_fma_f32 %[tv], %[nv], |%[rv]|, %[t0v]\n\t"                               \
+            "v_fma_f32 %[tz], %[nz], |%[rz]|, %[t0z]\n\t"
+#define MV_ASM_LOOP(CELL)                                                               \
+            "s_mov_b64 %[save], exec\n\t"                                               \
+            MV_ASM_TEST("%[t0v]", "%[t0z]", "%[ia]", "%[ib]", CELL)                      \
+            MV_ASM_LEAVE                                                                \
+            MV_ASM_FIRST_ADVANCE                                                        \
+            "1:\n\t"                                                                    \
+            MV_ASM_TEST("%[tv]", "%[tz]", "%[ib]", "%[ia]", CELL)                        \
+            "v_mov_b32_e32 %[ib], %[ia]\n\t"                                            \
+            MV_ASM_LEAVE                                                                \
+            MV_ASM_ADVANCE                                                              \
+            MV_ASM_TEST("%[tv]", "%[tz]", "%[ia]", "%[ib]", CELL)                        \
+            MV_ASM_LEAVE                                                                \
+            MV_ASM_ADVANCE                                                              \
+            "s_branch 1b\n"                                                             \
+            "2:\n\t"                                                                    \
+            "s_mov_b64 exec, %[save]\n\t"
+#define MV_ASM_OPERANDS                                                                                              \
+                : [save] "=&s"(exec_save), [mgo] "=&s"(m_go), [mempty] "=&s"(m_empty), [tout] "=&v"(t_out),            \
+                  [tmp] "=&v"(tmp), [sh] "=&v"(sh), [r] "=&v"(r), [inr] "=&v"(in_range), [ib] "=&v"(i_b),             \
+                  [tv] "=&v"(t_v), [tz] "=&v"(t_z), [ia] "+v"(i_a), [row] "+v"(row), [addr] "+v"(addr),               \
+                  [nv] "+v"(n_v), [nz] "+v"(n_z)                                                                      \
+                : [tend] "v"(t_end), [du] "v"(du), [pu] "v"(c.Pu), [sv] "v"(c.sv), [sz] "v"(c.sz), [rv] "v"(rcp_v),  \
+                  [rz] "v"(rcp_z), [t0v] "v"(t0_v), [t0z] "v"(t0_z), [um1] "v"(c.um1)                                 \
+                : "vcc", "memory"
+        if (kNarrow) asm volatile(MV_ASM_LOOP(MV_ASM_CELL_NARROW) MV_ASM_OPERANDS);
+        else         asm volatile(MV_ASM_LOOP(MV_ASM_CELL_WIDE) MV_ASM_OPERANDS);
+#undef MV_ASM_OPERANDS
+#undef MV_ASM_LOOP
+#undef MV_ASM_ADVANCE
+#undef MV_ASM_FIRST_ADVANCE
+#undef MV_ASM_NEXT_ROW
+#undef MV_ASM_LEAVE
+#undef MV_ASM_CELL_WIDE
+#undef MV_ASM_CELL_NARROW
+#undef MV_ASM_TEST
+        i_last = i_b;
     }
-#undef MV_ROW_TURN
     const bool found = in_range != 0;
 
     // in_range is r moved up so that cell i_last sits at bit 63: its lowest set bit p is cell i_last - (63 - p)
@@ -795,6 +867,10 @@ template <bool AUX, bool PACKED, bool FAST>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void render_kernel(RenderParams p)
 {
     extern __shared__ __align__(16) uint8_t lds[];
+    // A workgroup that has just arrived runs its staging at a raised wave priority (the tile loop returns to the
+    // default): its few instructions are issued ahead of the tracing waves it shares the SIMDs with, so its
+    // loads are on their way sooner.
+    __builtin_amdgcn_s_setprio(3);
     const int threads = p.threads;
     // LDS byte address of the dynamic segment: row addresses in the scan-class records are absolute
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
@@ -833,7 +909,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
     // LDS map, mirrors lds_map() on the host
     const uint32_t off_classes = 0;
-    const uint32_t off_scalars = kScanClasses * 80;
+    const uint32_t off_scalars = kScanClasses * kClassStride;
     const uint32_t off_lut = off_scalars + (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
     const uint32_t off_rows = off_lut + (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15);
     float* lds_sx = reinterpret_cast<float*>(lds + off_scalars);
@@ -912,27 +988,35 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         for (int i = tid + threads; i < p.H; i += threads) lds_sy[i] = p.sy[i];
         for (int i = tid + threads; i < lut_n; i += threads) ll[i] = gl[i];
     }
-    __syncthreads();
-
-    // This workgroup's copy of the rows is private to one camera: remove the camera's own body from it
-    // once, instead of testing for it at every step.
-    if (self_lo >= 0 && threadIdx.x < 2) {
-        int s = threadIdx.x == 0 ? self_lo : self_hi;
-        if (s >= 0 && s < X * Y * Z) {
-            int k = s / (X * Y), rem = s - k * X * Y, j = rem / X, i = rem - j * X;
-            if (FAST) {
-                if (use_rows && k < staged) {
-                    uint64_t* ax = lds_rows;
-                    uint64_t* axm = ax + sxw;
-                    uint64_t* ay = axm + sxw;
-                    uint64_t* aym = ay + syw;
-                    ax[k * Y + j] &= ~(1ull << i);
-                    axm[k * Y + j] &= ~(1ull << (X - 1 - i));
-                    ay[k * X + i] &= ~(1ull << j);
-                    aym[k * X + i] &= ~(1ull << (Y - 1 - j));
+    // This workgroup's copy of the rows is private to one camera: the camera's own body is removed from it
+    // once, instead of being tested for at every step.  The thread that staged a word (word index modulo the
+    // workgroup size) clears the body's bit in it straight after its own stores (one wave's LDS operations
+    // keep their order), so the barrier below is the only one the staging needs.
+    if (self_lo >= 0) {
+#pragma unroll
+        for (int part = 0; part < 2; ++part) {
+            const int sv_ = part == 0 ? self_lo : self_hi;
+            if (sv_ >= 0 && sv_ < X * Y * Z) {
+                const int k = sv_ / (X * Y), rem = sv_ - k * X * Y, j = rem / X, i = rem - j * X;
+                if (FAST) {
+                    if (use_rows && k < staged) {
+                        uint64_t* ax = lds_rows;
+                        uint64_t* axm = ax + sxw;
+                        uint64_t* ay = axm + sxw;
+                        uint64_t* aym = ay + syw;
+                        if ((int)threadIdx.x == (k * Y + j) % threads) {
+                            ax[k * Y + j] &= ~(1ull << i);
+                            axm[k * Y + j] &= ~(1ull << (X - 1 - i));
+                        }
+                        if ((int)threadIdx.x == (k * X + i) % threads) {
+                            ay[k * X + i] &= ~(1ull << j);
+                            aym[k * X + i] &= ~(1ull << (Y - 1 - j));
+                        }
+                    }
+                } else {
+                    const int w = (k * Y + j) * g.rowwords_x + (i >> 6);
+                    if ((int)threadIdx.x == w % threads) lds_rows[w] &= ~(1ull << (i & 63));
                 }
-            } else {
-                lds_rows[(k * Y + j) * g.rowwords_x + (i >> 6)] &= ~(1ull << (i & 63));
             }
         }
     }
@@ -978,7 +1062,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         c.stride_v = (float)(vneg ? -sv_idx : sv_idx);
         c.stride_z = (float)(zneg ? -X * Y : X * Y);
         c.idx0 = (float)(kc * X * Y + j0 * sv_idx + (neg ? (U - 1) * su : 0));
-        *reinterpret_cast<ScanClass*>(lds + off_classes + q * 80) = c;
+        *reinterpret_cast<ScanClass*>(lds + off_classes + q * kClassStride) = c;
     }
     __syncthreads();
 
@@ -1058,11 +1142,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         float pend_t = 0.0f;
         uint32_t pend_pix = 0;
         bool pend_active = false, pending = false;
+        // tile coordinates are carried along instead of divided out of the tile index every trip
+        int ty = (tile_begin + wave) / p.tiles_x, tx = (tile_begin + wave) - ty * p.tiles_x - waves;
         for (int tile = tile_begin + wave; tile < tile_end; tile += waves) {
             // lanes without a hit (idx -1 = 0xffffffff) read the last voxel and drop it later: no branch
             const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
 
-            const int ty = tile / p.tiles_x, tx = tile - ty * p.tiles_x;
+            tx += waves;
+            while (tx >= p.tiles_x) { tx -= p.tiles_x; ++ty; }
             // PACKED launches have W and H multiples of the tile size: every lane owns a pixel, and its
             // addresses are a per-lane constant plus a per-tile (wave-uniform) offset
             bool active = true;
