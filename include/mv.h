@@ -116,8 +116,9 @@ int mv_upload_worlds(mv_batch* batch, int32_t first_env, int32_t count, const ui
  *   env, voxel_index : [count] int32;  material : [count] uint8.  All three in host memory if
  *   src_is_device == 0 (validated: MV_ERR_RANGE for an environment, index or material id out of range,
  *   nothing is changed), else in device memory (not validated; out-of-range edits are dropped).
- * One call must not contain two edits of the same voxel (their order would be undefined); send the
- * clears and the sets of one step as two calls if an object may move into a voxel another one leaves.
+ * Within one call every edit that empties a voxel (material 0) is applied before every edit that fills one,
+ * whatever their order in the list: an object may move into the voxel another one leaves in the same step.
+ * Two fills of the same voxel in one call are not ordered (either material may win).
  * The occupancy bit rows are patched in place with atomics; the per-environment "highest solid layer"
  * bound only grows (it stays a valid bound when the top voxel is removed).  count == 0 is a no-op.
  * Errors: MV_ERR_ARG, MV_ERR_RANGE, MV_ERR_STATE (an addressed environment has no grid yet; host data
@@ -132,7 +133,8 @@ int mv_update_voxels(mv_batch* batch, int32_t count, const int32_t* env, const i
  *                -1 for none; NULL means -1 everywhere.
  * Host memory if src_is_device == 0 (validated: non-finite value -> MV_ERR_ARG), else device
  * memory (not validated).  The camera basis is computed on the GPU in float64 and rounded to
- * float32 records on `stream`.  Errors: MV_ERR_ARG, MV_ERR_HIP. */
+ * float32 records on `stream`.  Errors: MV_ERR_ARG, MV_ERR_RANGE (a self_voxel outside the grid; host data
+ * only), MV_ERR_HIP. */
 int mv_set_cameras(mv_batch* batch, const float* cams, const int32_t* self_voxel,
                    int32_t src_is_device, void* hip_stream);
 
@@ -145,7 +147,11 @@ int mv_set_cameras(mv_batch* batch, const float* cams, const int32_t* self_voxel
  * One kernel launch on `stream`; returns without synchronising.  The kernel keeps the lowest layers of each
  * grid on chip, as many as the tallest world uploaded so far needs (learnt from earlier kernels without
  * synchronising); the first launch after taller worlds arrive renders them through device memory (slower,
- * same accuracy, not necessarily the same bits at exact ties), later launches adapt.
+ * same accuracy, not necessarily the same bits at exact ties), later launches adapt.  While `stream` is being
+ * captured into a HIP graph that choice would be frozen into the graph, so a captured launch keeps ALL layers
+ * on chip instead (a few per cent slower than the adaptive choice on low worlds, never the slow path on a
+ * replay over taller ones); a caller who knows the tallest world the graph will ever see can fix a smaller
+ * number with mv_debug_set_staged_layers before capturing.
  * Errors: MV_ERR_ARG, MV_ERR_STATE (some environment or the cameras never supplied), MV_ERR_HIP. */
 int mv_render_batch(mv_batch* batch, uint8_t* rgb, float* depth, uint8_t* aux_material,
                     int32_t* aux_hit_index, uint8_t* aux_face, void* hip_stream);
@@ -188,7 +194,9 @@ int mv_draw_bars(mv_batch* batch, uint8_t* rgb, const float* fraction, const mv_
  * validated; nothing is copied to the host, allocated or waited for, so the call can be captured in a
  * HIP graph.  The caller resets a finished environment by uploading its next world (mv_upload_worlds with
  * first_env, count) before the step in which it is no longer flagged.  The inactive set stays in force for
- * later mv_render_batch / mv_draw_bars calls until mv_set_active or the next mv_step replaces it. */
+ * later mv_render_batch / mv_draw_bars calls until mv_set_active or the next mv_step replaces it.  The edit list
+ * follows the rule of mv_update_voxels (all clears before all fills, one fill per voxel); a captured step keeps
+ * all grid layers on chip (see mv_render_batch). */
 typedef struct {
     int32_t        num_edits;      /* voxel edits of this step, >= 0                                   */
     const int32_t* edit_env;       /* [num_edits] environment of each edit; may be NULL if num_edits == 0 */

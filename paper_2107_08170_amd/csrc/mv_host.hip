@@ -454,11 +454,26 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     // so far (read without synchronising: a value that is out of date costs speed, never correctness -- a
     // workgroup whose world is taller than what was staged traces through global memory and reports it),
     // all of them before the first report.
+    // A launch that is being captured into a HIP graph will be replayed later, over worlds this call cannot
+    // know: it stages every layer (unless the caller fixed the number), so that a replay never falls back to the
+    // slow path because the worlds grew after the capture.
     int staged = b->cfg.grid_z;
     if (b->layout.fast) {
-        // one layer above the tallest world: cameras that fly above their world stand in that (empty) layer
-        const int seen = b->forced_layers > 0 ? b->forced_layers : *(volatile int32_t*)b->h_height + 1;
-        if (seen > 1 && seen < staged) staged = seen;
+        bool capturing = false;
+        if (hip_stream) {
+            hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing((hipStream_t)hip_stream, &status) == hipSuccess)
+                capturing = status == hipStreamCaptureStatusActive;
+            else
+                (void)hipGetLastError();
+        }
+        if (b->forced_layers > 0) {
+            staged = b->forced_layers;
+        } else if (!capturing) {
+            // one layer above the tallest world: cameras that fly above their world stand in that (empty) layer
+            const int seen = *(volatile int32_t*)b->h_height + 1;
+            if (seen > 1 && seen < staged) staged = seen;
+        }
     }
     const mv::LdsPlan plan = mv::plan_lds(b->layout, b->cfg.width, b->cfg.height, b->materials_plus_one, staged);
 

@@ -397,7 +397,11 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
 // update: one thread per edited voxel.  The material byte is overwritten; the voxel's bit in its x row
 // and in its y row is set or cleared with a 64-bit atomic (several edits of one call may share a row
 // word); setting a voxel raises the environment's top-layer bound, clearing never lowers it.
+// Two launches per call: kFill == false applies the edits that empty a voxel, kFill == true, after it in
+// stream order, those that fill one -- so an object that moves into the voxel another one leaves in the
+// same step ends up there whatever the order of the two edits in the list.
 // ------------------------------------------------------------------------------------------
+template <bool kFill>
 __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int32_t* __restrict__ voxel_index,
                                      const uint8_t* __restrict__ material, int count, uint8_t* __restrict__ vox,
                                      uint64_t* __restrict__ bits, int32_t* __restrict__ ztop, int num_envs,
@@ -407,6 +411,7 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
     if (e >= count) return;
     const int n = env[e], idx = voxel_index[e];
     const int m = material[e];
+    if ((m != 0) != kFill) return;
     if (n < 0 || n >= num_envs || idx < 0 || idx >= voxels_per_env || m > num_materials) return;
     const int XY = g.X * g.Y;
     const int k = idx / XY, rem = idx - k * XY, j = rem / g.X, i = rem - j * g.X;
@@ -415,7 +420,7 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
                                ((size_t)k * g.Y + j) * g.rowwords_x + (i >> 6);
     unsigned long long* yrow = reinterpret_cast<unsigned long long*>(bits) + (size_t)n * g.env_words + g.xrow_words +
                                ((size_t)k * g.X + i) * g.rowwords_y + (j >> 6);
-    if (m != 0) {
+    if (kFill) {
         atomicOr(xrow, 1ull << (i & 63));
         atomicOr(yrow, 1ull << (j & 63));
         if (atomicMax(ztop + n, k + 1) < k + 1) report_height(heights, k + 1);
@@ -429,7 +434,9 @@ hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, 
                                 uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
                                 int num_materials, const GridLayout& g, const HeightFeedback& heights, hipStream_t stream)
 {
-    hipLaunchKernelGGL(update_voxels_kernel, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
+    hipLaunchKernelGGL(update_voxels_kernel<false>, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
+                       material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g, heights);
+    hipLaunchKernelGGL(update_voxels_kernel<true>, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
                        material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g, heights);
     return hipGetLastError();
 }
@@ -938,7 +945,15 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     // Row scan: only if those layers were staged.  The launch stages as many layers as the tallest world
     // the host has heard of; a taller one is traced through the rows in global memory, cell by cell, and
     // says so, so that the next launch stages enough.
-    const int staged = FAST ? p.staged_layers : Z;
+    // Layers kept on chip: the launch reserved LDS for p.staged_layers of them; the batch's device word says how
+    // tall the tallest world really is right now (it is exact: written by the pack and edit kernels earlier in the
+    // stream), and nothing above that plus the one empty layer on top is worth copying.  A launch whose size was
+    // fixed long before it runs (a replayed graph) thus stages only what today's worlds need.
+    int staged = FAST ? p.staged_layers : Z;
+    if (FAST && p.heights.device_max) {
+        const int tallest = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.heights.device_max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        staged = min(staged, max(tallest + 1, 1));
+    }
     const bool use_rows = FAST && origin_in_grid && zlim <= staged;
     const int sxw = staged * Y, syw = staged * X;          // words of one staged x / y row array
     if (FAST && origin_in_grid && !use_rows && threadIdx.x == 0 && p.heights.device_max) {

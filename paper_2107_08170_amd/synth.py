@@ -300,6 +300,37 @@ def generate(index: int, num_envs: Optional[int] = None, steps: Optional[int] = 
     return _gen_arena(spec, rng)
 
 
+# Workloads for the render paths the five headline workloads never take (same arena recipe, mid-size batches):
+#   wide    : grids wider than 64 voxels (rows of more than one word): the per-cell tracer over rows staged on chip
+#   outside : cameras outside the grid, looking in: the per-cell tracer over rows in device memory
+#   odd     : an image whose width and height are not multiples of the 8x8 tile: clamped tiles and byte stores
+EXTRA_SPECS = {
+    "wide": WorkloadSpec("wide_256x2_96x96x16", 5, 256, 2, (96, 96, 16), 128, 72, 16, 1),
+    "outside": WorkloadSpec("outside_256x4_40x40x16", 6, 256, 4, (40, 40, 16), 128, 72, 16, 1),
+    "odd": WorkloadSpec("odd_256x4_40x40x16_130x70", 7, 256, 4, (40, 40, 16), 130, 70, 16, 1),
+}
+
+
+def generate_extra(name: str) -> Workload:
+    """One of the EXTRA_SPECS workloads (seed = BASE_SEED + its index)."""
+    spec = EXTRA_SPECS[name]
+    rng = _rng(spec.index)
+    wl = _gen_arena(spec, rng)
+    if name == "outside":
+        # every camera on a ring around its arena, above the walls, looking at the middle (give or take)
+        N, A = spec.num_envs, spec.agents_per_env
+        X, Y, Z = spec.grid
+        n = N * A
+        around = rng.uniform(0.0, 2.0 * np.pi, size=n)
+        radius = rng.uniform(0.6 * X, 0.95 * X, size=n)
+        pos = np.stack([X / 2 + radius * np.cos(around), Y / 2 + radius * np.sin(around),
+                        rng.uniform(2.0, Z - 2.0, size=n)], axis=1)
+        yaw = around + np.pi + rng.uniform(-0.3, 0.3, size=n)
+        pitch = rng.uniform(-0.45, 0.05, size=n)
+        wl.cameras = np.concatenate([pos, yaw[:, None], pitch[:, None]], axis=1).astype(np.float32)[None]
+    return wl
+
+
 def random_world(rng: np.random.Generator, N: int, grid: Tuple[int, int, int], fill: float,
                  M: int) -> Tuple[np.ndarray, np.ndarray]:
     """Unstructured worlds (i.i.d. occupancy with probability ``fill``) for edge-case tests:

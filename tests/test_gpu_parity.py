@@ -922,6 +922,162 @@ def test_step_replays_from_a_hip_graph(lib, orc):
     parity.compare(run_g.numpy(), ob.render(threads=8), label="graph replay, last step")
 
 
+# ------------------------------------------------------------------------------------------ the other render paths, at scale
+@pytest.mark.parametrize("name", ["wide", "outside", "odd"])
+def test_slow_paths_on_mid_size_batches(lib, orc, name):
+    """Every pixel against the oracle on batches of hundreds of observations for the paths the five workloads
+    never take: grids wider than 64 voxels (per-cell tracer over rows on chip), cameras outside the grid (per-cell
+    tracer over rows in device memory), and an image that is not made of whole 8x8 tiles (clamped tiles, byte
+    stores) -- several workgroups per compute unit, tail strips and the XCD mapping included."""
+    wl = synth.generate_extra(name)
+    spec = wl.spec
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
+    run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0])
+    run.render()
+    st = _compare_all(ob, run, label=name, chunk=256)
+    assert st["pixels"] == spec.num_obs * spec.height * spec.width
+    if name == "outside":
+        assert (run.depth > 0).float().mean().item() > 0.2          # the cameras do look at their arenas
+
+
+def test_step_captured_over_low_worlds_replays_over_taller_ones(lib, orc):
+    """A graph captured while every world is two layers tall must still render at full speed, and correctly,
+    when taller worlds are uploaded afterwards: the captured launch reserves room for all layers instead of the
+    number that happened to be enough at capture time.  Replay vs oracle, and replay time vs the eager call, on
+    the benchmark's batch (4096 environments x 2 agents: a step long enough that the few microseconds a replay
+    costs by itself do not decide the comparison)."""
+    wl = synth.generate(2, steps=1)
+    spec = wl.spec
+    low = wl.voxels.copy()
+    low[:, 2:] = 0                                                  # floor + one layer of walls
+    batch = binding.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height)
+    run = GpuRender(batch, spec.width, spec.height, aux=False)
+    low_d, tall_d = torch.from_numpy(low).cuda(), torch.from_numpy(wl.voxels).cuda()
+    pal_d = torch.from_numpy(wl.palette).cuda()
+    cams_in = torch.from_numpy(wl.cameras[0]).cuda()
+    batch.upload_worlds(low_d, pal_d, stream=_stream())
+    batch.set_cameras(cams_in, stream=_stream())
+    run.render()
+    torch.cuda.synchronize()                                        # the host has now heard: worlds are 2 layers tall
+    run.render()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            batch.step(cams_in, run.rgb, run.depth, stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    ob_low = _oracle_for(orc, spec, low, wl.palette, wl.cameras[0])
+    _compare_all(ob_low, run, label="replay over the low worlds", chunk=512)
+    # taller worlds arrive
+    batch.upload_worlds(tall_d, pal_d, stream=_stream())
+    torch.cuda.synchronize()
+    run.rgb.fill_(7); run.depth.fill_(-1.0)
+    graph.replay()
+    torch.cuda.synchronize()
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
+    _compare_all(ob, run, label="replay over the taller worlds", chunk=512)
+
+    def timed(fn, reps=100):
+        for _ in range(30):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    t_eager = timed(lambda: batch.step(cams_in, run.rgb, run.depth, stream=_stream()))
+    t_graph = timed(graph.replay)
+    # Room for all layers costs a workgroup or two per compute unit against the eager call's ten layers; the path
+    # through device memory that a frozen two-layer choice would take is several times slower.
+    assert t_graph <= 1.10 * t_eager, (t_graph, t_eager)
+    # a caller who knows how tall the worlds can get fixes the number before capturing: then the replay runs the
+    # very launch the eager call makes
+    batch.debug_set_staged_layers(10)
+    pinned = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(pinned, stream=side):
+            batch.step(cams_in, run.rgb, run.depth, stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    run.rgb.fill_(7); run.depth.fill_(-1.0)
+    pinned.replay()
+    torch.cuda.synchronize()
+    _compare_all(ob, run, label="replay with a fixed layer count", chunk=512)
+    t_pinned = timed(pinned.replay)
+    assert t_pinned <= 1.05 * t_eager, (t_pinned, t_eager)
+    batch.debug_set_staged_layers(0)
+
+
+def test_an_object_enters_the_voxel_another_one_leaves_in_the_same_call(lib, orc):
+    """One edit list that empties a voxel and fills the same voxel again (object 1 leaves, object 2 enters),
+    next to ordinary moves: clears are applied before fills whatever their order in the list, so the voxel ends
+    up solid with the new material, its occupancy bit set -- as the oracle's in-order edits give for the order
+    (clear, fill), and the same for the order (fill, clear) of a per-object list."""
+    wl = synth.generate(1, num_envs=8)
+    spec = wl.spec
+    X, Y, Z = spec.grid
+    vox = wl.voxels.copy()
+    cams = wl.cameras[0]
+    # put a box right in front of camera 0 of every environment, then swap it for a box of another material
+    env, idx, mat_old, mat_new = [], [], [], []
+    for n in range(spec.num_envs):
+        c = cams[n * spec.agents_per_env]
+        i, j = int(c[0]), int(c[1])
+        for di, dj in ((1, 0), (-1, 0), (0, 1), (0, -1)):
+            ii, jj = i + 2 * di, j + 2 * dj
+            if 1 <= ii < X - 1 and 1 <= jj < Y - 1 and vox[n, 1, jj, ii] == 0:
+                env.append(n); idx.append((1 * Y + jj) * X + ii); mat_old.append(3); mat_new.append(9)
+                vox[n, 1, jj, ii] = 3
+                break
+    assert len(env) >= 4
+    env = np.array(env, np.int32); idx = np.array(idx, np.int32)
+    run = _gpu_for(spec, vox, wl.palette, cams)
+    ob = _oracle_for(orc, spec, vox, wl.palette, cams)
+    for order in ("clear first", "fill first"):
+        clear = (env, idx, np.zeros(len(env), np.uint8))
+        fill = (env, idx, np.array(mat_new, np.uint8))
+        first, second = (clear, fill) if order == "clear first" else (fill, clear)
+        e = np.concatenate([first[0], second[0]]); v = np.concatenate([first[1], second[1]])
+        m = np.concatenate([first[2], second[2]])
+        run.batch.update_voxels(torch.from_numpy(e).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(m).cuda(),
+                                stream=_stream())
+        ob.update_voxels(*clear)                                    # the oracle applies edits in list order
+        ob.update_voxels(*fill)
+        run.render()
+        st = parity.compare(run.numpy(), ob.render(threads=8), label=order)
+        assert st["pixels"] > 0
+        hit_new = run.numpy().material == 9
+        assert hit_new.any(), order                                 # the new boxes are seen, with their material
+        # back to the old material for the second order
+        back = (env, idx, np.array(mat_old, np.uint8))
+        run.batch.update_voxels(*(torch.from_numpy(a).cuda() for a in back), stream=_stream())
+        ob.update_voxels(*back)
+
+
+def test_upload_of_the_largest_layer_the_pack_kernel_holds(lib, orc):
+    """200x200x2: each of the pack kernel's four waves keeps a whole 40,000-byte layer in LDS, just under the
+    limit checked at creation; the packed rows and a small render must be right."""
+    grid = (200, 200, 2)
+    rng = np.random.default_rng(11)
+    N, A, M = 2, 2, 5
+    spec = _mini_spec(N, A, grid, 64, 40, M)
+    vox, pal = synth.random_world(rng, N, grid, 0.05, M)
+    vox[:, 0] = np.where(vox[:, 0] == 0, 1, vox[:, 0])               # a floor
+    cams = synth.random_cameras(rng, N * A, grid, margin=0.0, max_pitch=0.6)
+    cams[:, 2] = 1.5
+    for o in range(N * A):
+        vox[o // A, 1, int(cams[o, 1]), int(cams[o, 0])] = 0           # the cameras stand in empty cells
+    ob = _oracle_for(orc, spec, vox, pal, cams)
+    run = _gpu_for(spec, vox, pal, cams)
+    run.render()
+    parity.compare(run.numpy(), ob.render(threads=8), label="200x200x2")
+
+
 # ------------------------------------------------------------------------------------------ pieces
 def _read_device(ptr, nbytes):
     hip = C.CDLL("libamdhip64.so")
