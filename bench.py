@@ -9,8 +9,17 @@ camera records (mv_set_cameras, a fresh camera set every step) and the render
 (mv_render_batch) of every observation.  Prints ONE JSON line: observations/s (whole job), the
 roofline of the dominant kernel measured with HIP events around every render launch, and the CPU
 oracle timed on a bounded sample of the same workload on the host cores.
+
+Order of the run: all inputs are generated and copied to the device first; a "cold start" sample (the first 20
+steps after that idle time) is taken; then the side measurements that use the GPU run: the other workloads, a
+plain device copy, and the cameras + render protocol on the headline batch (100 steps).  The headline region (W
+warm-up steps, K timed steps) follows them directly: a GPU that has been idle runs this kernel 10-25 % slower
+for its first fifty to a hundred launches (about 25 ms), whatever the warm-up count, and the sustained rate is
+what the metric asks for; the cold figure is reported next to it.  Delivery to host memory and the CPU oracle
+come last.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -26,9 +35,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E datasheet peak
 # multiply, move, and, right shifts) can reach it; min/max, compares, selects, conversions and 64-bit shifts
 # issue at half of it (profiles/valu_instruction_rates.txt), and they are most of a ray traversal.
 ALU_PEAK_GOPS = 256 * 4 * 32 * 2.4     # 78643.2 G lane-instructions/s
-# Mean per-cell DDA steps per ray of the CPU oracle on camera set 0 of each workload (measured with the
-# oracle's step counter on the first 256/512/256/128 environments); the cpu_baseline leg re-measures it.
-ORACLE_MEAN_STEPS = {1: 8.75, 2: 8.98, 3: 8.45, 4: 10.20}
+LDS_PEAK_GBS = 256 * 128 * 2.4         # 256 CUs x 128 bytes per clock x 2.4 GHz
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2107_08170_amd", "csrc", "mv_kernels.hip")
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "render_traffic.txt")
+STEPS_PROFILE = os.path.join(ROOT, "profiles", "oracle_mean_steps.txt")
 
 
 def algorithmic_lane_ops_per_ray(mean_steps: float) -> float:
@@ -50,17 +60,41 @@ def algorithmic_bytes_per_obs(spec) -> float:
     return rays * 7 + rays * 1 + (occ_bytes + lut_bytes) / spec.agents_per_env + 64
 
 
-def measured_traffic(workload: str, column: int = 1):
-    """Bytes per render launch from the committed rocprofv3 counter summary: column 1 = HBM (FETCH_SIZE and
-    WRITE_SIZE scaled against a plain copy), column 2 = LDS (from SQ_INSTS_LDS); None when no summary covers
-    this workload.  Column 3 = vector lane-instructions executed per launch (SQ_INSTS_VALU x 64)."""
-    path = os.path.join(ROOT, "profiles", "render_traffic.txt")
+def kernel_source_sha256() -> str:
+    with open(KERNEL_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
+def profiled_counters(workload: str):
+    """Per-launch counter figures of the render kernel from the committed rocprofv3 summary: HBM bytes (FETCH_SIZE
+    and WRITE_SIZE scaled against a plain copy), LDS bytes (from SQ_INSTS_LDS) and vector lane-instructions
+    executed (SQ_INSTS_VALU x 64).  The summary names the SHA-256 of the kernel source it was measured on; when
+    that is not the source of the library being timed, the figures are stale and nothing is returned."""
     try:
-        with open(path) as f:
-            for line in f:
-                parts = line.split()
-                if len(parts) > column and parts[0] == workload:
-                    return float(parts[column])
+        with open(TRAFFIC_PROFILE) as f:
+            lines = f.read().splitlines()
+    except OSError:
+        return None
+    sha = next((ln.split()[-1] for ln in lines if ln.startswith("# kernel_source_sha256")), None)
+    if sha != kernel_source_sha256():
+        return None
+    for ln in lines:
+        parts = ln.split()
+        if len(parts) >= 4 and parts[0] == workload:
+            return {"hbm_bytes": float(parts[1]), "lds_bytes": float(parts[2]), "valu_lane_ops": float(parts[3]),
+                    "kernel_source_sha256": sha}
+    return None
+
+
+def committed_mean_steps(workload: str):
+    """Mean per-cell DDA steps per ray of the CPU oracle on camera set 0, from the committed summary written by
+    ``python -m oracle.mean_steps`` (used only when this run skips its own oracle pass)."""
+    try:
+        with open(STEPS_PROFILE) as f:
+            for ln in f:
+                parts = ln.split()
+                if len(parts) >= 2 and parts[0] == workload:
+                    return float(parts[1])
     except OSError:
         pass
     return None
@@ -68,7 +102,6 @@ def measured_traffic(workload: str, column: int = 1):
 
 def input_digest(wl) -> str:
     """SHA-256 over the generated grids, palettes and cameras: identifies the synthetic input of a run."""
-    import hashlib
     import numpy as np
     h = hashlib.sha256()
     for a in (wl.voxels, wl.palette, wl.cameras):
@@ -92,12 +125,163 @@ def device_copy_rate(torch) -> float:
     return 2.0 * nbytes * 5 / (a.elapsed_time(b) * 1e-3) / 1e9
 
 
+class Leg:
+    """One workload resident on the device: batch object, inputs of a few steps, output tensors."""
+
+    def __init__(self, mv, synth, torch, np, wl, index, sparse_edits=False, tiles_per_block=0):
+        spec = wl.spec
+        dev = torch.device("cuda", 0)
+        self.torch, self.np, self.spec, self.wl = torch, np, spec, wl
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.batch = mv.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height,
+                              tiles_per_block=tiles_per_block)
+        self.pal_d = torch.from_numpy(wl.palette).to(dev)
+        self.sparse = bool(sparse_edits and spec.dynamic)
+        self.edits_d = []
+        if spec.dynamic:
+            # dynamic worlds: pre-compute the grids/cameras of a few steps on the host, keep them resident
+            grids, cams_l, self_l = [wl.voxels], [wl.cameras[0]], [wl.self_voxel[0]]
+            for _ in range(3):
+                g, c, s = synth.dynamic_step(wl)
+                grids.append(g); cams_l.append(c); self_l.append(s)
+            self.grids_d = [torch.from_numpy(g).to(dev) for g in grids]
+            self.cams_d = torch.from_numpy(np.stack(cams_l)).to(dev)
+            self.self_d = torch.from_numpy(np.stack(self_l)).to(dev)
+            self.first_grid, self.first_cams, self.first_self = grids[0], cams_l[0], self_l[0]
+            if self.sparse:                   # edits that turn grid k-1 into grid k (cyclically)
+                for k in range(len(grids)):
+                    e, i, m = synth.grid_edits(grids[k - 1], grids[k])
+                    self.edits_d.append(tuple(torch.from_numpy(a).to(dev) for a in (e, i, m)))
+        else:
+            cams_np = wl.cameras
+            if cams_np.shape[0] < 8:
+                # single-pose workloads: re-draw view angles so that every timed step renders new cameras
+                rng = np.random.default_rng(synth.BASE_SEED + 100 + index)
+                cams_np = np.repeat(cams_np[:1], 8, axis=0).copy()
+                if index in (s.index for s in synth.EXTRA_SPECS.values()):
+                    # these cameras are aimed (the outside ones at their arena): turn them a little only
+                    cams_np[1:, :, 3] += rng.uniform(-0.3, 0.3, size=cams_np[1:, :, 3].shape)
+                    cams_np[1:, :, 4] += rng.uniform(-0.1, 0.1, size=cams_np[1:, :, 4].shape)
+                else:
+                    cams_np[1:, :, 3] = rng.uniform(0, 2 * np.pi, size=cams_np[1:, :, 3].shape)
+                    cams_np[1:, :, 4] = rng.uniform(-np.pi / 6, np.pi / 6, size=cams_np[1:, :, 4].shape)
+            self.cams_d = torch.from_numpy(cams_np).to(dev)
+            self.grids_d, self.self_d = [torch.from_numpy(wl.voxels).to(dev)], None
+            self.first_grid, self.first_cams, self.first_self = wl.voxels, cams_np[0], None
+        self.n_sets = int(self.cams_d.shape[0])
+        n, H, W = spec.num_obs, spec.height, spec.width
+        self.rgb = torch.empty((n, H, W, 3), dtype=torch.uint8, device=dev)
+        self.depth = torch.empty((n, H, W), dtype=torch.float32, device=dev)
+
+    def step(self, i, ev=None, static_worlds=False, rgb=None, depth=None, stream=None):
+        stream = self.stream if stream is None else stream
+        k = i % self.n_sets
+        if self.sparse and i > 0:
+            self.batch.update_voxels(*self.edits_d[k], stream=stream)
+        elif not static_worlds or i == 0:
+            self.batch.upload_worlds(self.grids_d[k % len(self.grids_d)], self.pal_d, stream=stream)
+        self.batch.set_cameras(self.cams_d[k], None if self.self_d is None else self.self_d[k], stream=stream)
+        if ev is not None:
+            ev[0].record()
+        self.batch.render(self.rgb if rgb is None else rgb, self.depth if depth is None else depth, stream=stream)
+        if ev is not None:
+            ev[1].record()
+
+    def timed(self, steps, warmup, static_worlds=False):
+        """`warmup` untimed steps, then exactly `steps` timed ones between two synchronisations; the render launch
+        of every timed step is bracketed by events on the launch stream."""
+        torch, np = self.torch, self.np
+        self.step(0)
+        for i in range(warmup):
+            self.step(i, static_worlds=static_worlds)
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(i if not static_worlds else i + 1, events[i], static_worlds=static_worlds)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        render_ms = np.array([a.elapsed_time(b) for a, b in events])
+        return elapsed, render_ms
+
+    def step_name(self, static_worlds=False):
+        if static_worlds:
+            return "mv_set_cameras(device) + mv_render_batch (worlds uploaded once)"
+        if self.sparse:
+            return "mv_update_voxels(device) + mv_set_cameras(device) + mv_render_batch"
+        return "mv_upload_worlds(device) + mv_set_cameras(device) + mv_render_batch"
+
+    def close(self):
+        self.batch.close()
+
+
+def side_workload(mv, synth, torch, np, wl, index, steps=40, warmup=15, sparse_edits=False):
+    """obs/s, rays/s and render time of another workload under the same step definition (a shorter region)."""
+    leg = Leg(mv, synth, torch, np, wl, index, sparse_edits=sparse_edits)
+    elapsed, render_ms = leg.timed(steps, warmup)
+    spec = wl.spec
+    out = {"workload": spec.name, "grid": list(spec.grid), "image": [spec.width, spec.height],
+           "observations_per_step": spec.num_obs, "step": leg.step_name(), "steps": steps, "warmup": warmup,
+           "obs_per_s": spec.num_obs * steps / elapsed,
+           "rays_per_s": spec.num_obs * steps / elapsed * spec.width * spec.height,
+           "ms_per_step": elapsed * 1e3 / steps, "render_kernel_ms": float(render_ms.mean()),
+           "render_hbm_fraction": algorithmic_bytes_per_obs(spec) * spec.num_obs / (render_ms.mean() * 1e-3) / 1e9
+                                  / HBM_PEAK_GBS}
+    leg.close()
+    del leg
+    torch.cuda.empty_cache()
+    return out
+
+
+def host_delivery(mv, torch, leg, steps=12):
+    """Observations/s that reach host memory: the step runs on one stream into one of two sets of output tensors
+    while the previous step's observations are copied to pinned host memory on a second stream
+    (mv_fetch_observations), the way a CPU consumer would be fed."""
+    spec = leg.spec
+    n, H, W = spec.num_obs, spec.height, spec.width
+    rgb2, depth2 = torch.empty_like(leg.rgb), torch.empty_like(leg.depth)
+    outs = [(leg.rgb, leg.depth), (rgb2, depth2)]
+    pinned = [(mv.PinnedBuffer(n * H * W * 3), mv.PinnedBuffer(n * H * W * 4)) for _ in range(2)]
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    rendered = [torch.cuda.Event() for _ in range(2)]
+    copied = [torch.cuda.Event() for _ in range(2)]
+    torch.cuda.synchronize()
+
+    def one(i):
+        b = i % 2
+        compute.wait_event(copied[b])                      # the buffer's last copy has left it
+        leg.step(i, rgb=outs[b][0], depth=outs[b][1], stream=compute.cuda_stream)
+        rendered[b].record(compute)
+        copy.wait_event(rendered[b])
+        leg.batch.fetch_observations(outs[b][0], outs[b][1], 0, n, pinned[b][0].address, pinned[b][1].address,
+                                     stream=copy.cuda_stream)
+        copied[b].record(copy)
+
+    for b in range(2):
+        copied[b].record(copy)
+    for i in range(3):
+        one(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for pr, pd in pinned:
+        pr.close(); pd.close()
+    bytes_per_step = n * H * W * 7
+    return {"obs_per_s": n * steps / elapsed, "ms_per_step": elapsed * 1e3 / steps, "steps": steps,
+            "device_to_host_GBs": bytes_per_step * steps / elapsed / 1e9,
+            "protocol": "mv_upload_worlds + mv_set_cameras + mv_render_batch on one stream, mv_fetch_observations of "
+                        "all observations (colour + depth) into pinned host memory on a second stream, two sets of "
+                        "output tensors"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # defaults: the shader clock needs about a hundred launches after idle to settle (the first launches of a
-    # run are up to 25 % slower), so the warm-up covers that and the timed region is long enough to average
-    # the rest out; the whole timed region still lasts well under a second
+    # defaults: long enough to average launch-to-launch variation out; the whole timed region still lasts well
+    # under a second
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", type=int, default=2, help="workload index 1..4 (default 2: 4096 envs x 2 agents)")
@@ -105,10 +289,13 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-envs", type=int, default=4096)
     ap.add_argument("--static-worlds", action="store_true",
-                    help="upload the worlds once instead of every step (not the headline number)")
+                    help="headline region with the worlds uploaded once instead of every step (not the headline number)")
     ap.add_argument("--sparse-edits", action="store_true",
                     help="dynamic workload only: send the changed voxels of each step with mv_update_voxels instead "
                          "of re-uploading whole grids")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the side measurements on the other workloads (profiling runs)")
+    ap.add_argument("--no-host-delivery", action="store_true", help="skip the delivery-to-host-memory measurement")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy five times, for scaling the HBM byte "
                          "counters of a rocprofv3 --pmc run against a kernel of known traffic")
@@ -138,74 +325,39 @@ def main() -> int:
         return 0
     mv.load_library()
 
+    # ---- inputs: everything is generated before the GPU is asked for anything
     spec = synth.SPECS[args.config]
     t0 = time.time()
     wl = synth.generate(args.config)
     gen_s = time.time() - t0
-    dev = torch.device("cuda", 0)
-    stream = torch.cuda.current_stream().cuda_stream
-    batch = mv.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height,
-                     tiles_per_block=args.tiles_per_block)
-    vox_d = torch.from_numpy(wl.voxels).to(dev)
-    pal_d = torch.from_numpy(wl.palette).to(dev)
-    n_sets = max(1, spec.steps)
-    if spec.dynamic:
-        # dynamic worlds: pre-compute the grids/cameras of a few steps on the host, keep them resident
-        n_sets = 4
-        grids, cams_l, self_l = [wl.voxels], [wl.cameras[0]], [wl.self_voxel[0]]
-        for _ in range(n_sets - 1):
-            g, c, s = synth.dynamic_step(wl)
-            grids.append(g); cams_l.append(c); self_l.append(s)
-        grids_d = [torch.from_numpy(g).to(dev) for g in grids]
-        cams_d = torch.from_numpy(np.stack(cams_l)).to(dev)
-        self_d = torch.from_numpy(np.stack(self_l)).to(dev)
-        edits_d = []
-        if args.sparse_edits:                 # edits that turn grid k-1 into grid k (cyclically)
-            for k in range(n_sets):
-                e, i, m = synth.grid_edits(grids[k - 1], grids[k])
-                edits_d.append(tuple(torch.from_numpy(a).to(dev) for a in (e, i, m)))
-    else:
-        cams_np = wl.cameras
-        if cams_np.shape[0] < 8:
-            # single-pose workloads: re-draw view angles so that every timed step renders new cameras
-            rng = np.random.default_rng(synth.BASE_SEED + 100 + args.config)
-            n_sets = 8
-            cams_np = np.repeat(cams_np[:1], n_sets, axis=0).copy()
-            cams_np[1:, :, 3] = rng.uniform(0, 2 * np.pi, size=cams_np[1:, :, 3].shape)
-            cams_np[1:, :, 4] = rng.uniform(-np.pi / 6, np.pi / 6, size=cams_np[1:, :, 4].shape)
-        n_sets = cams_np.shape[0]
-        cams_d = torch.from_numpy(cams_np).to(dev)
-        grids_d, self_d = [vox_d], None
-
+    with_others = args.config == 2 and not args.no_other_workloads and not args.static_worlds and not args.sparse_edits
+    others = []
+    if with_others:
+        others = [(c, synth.generate(c), False) for c in (1, 3, 4)]
+        others.insert(2, (3, synth.generate(3), True))
+        others += [(s.index, synth.generate_extra(name), False) for name, s in synth.EXTRA_SPECS.items()]
+    leg = Leg(mv, synth, torch, np, wl, args.config, sparse_edits=args.sparse_edits, tiles_per_block=args.tiles_per_block)
     n, H, W = spec.num_obs, spec.height, spec.width
-    rgb = torch.empty((n, H, W, 3), dtype=torch.uint8, device=dev)
-    depth = torch.empty((n, H, W), dtype=torch.float32, device=dev)
 
-    def step(i, ev=None):
-        k = i % n_sets
-        if args.sparse_edits and spec.dynamic and i > 0:
-            batch.update_voxels(*edits_d[k], stream=stream)
-        elif not args.static_worlds or i == 0:
-            batch.upload_worlds(grids_d[k % len(grids_d)], pal_d, stream=stream)
-        batch.set_cameras(cams_d[k], None if self_d is None else self_d[k], stream=stream)
-        if ev is not None:
-            ev[0].record()
-        batch.render(rgb, depth, stream=stream)
-        if ev is not None:
-            ev[1].record()
+    # ---- the first steps after the idle time of the set-up, for the record
+    cold_el, cold_rm = leg.timed(20, 0)
 
-    step(0)
-    for i in range(args.warmup):
-        step(i)
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, events[i])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    # ---- side measurements that keep the GPU busy right up to the headline region
+    other_results = []
+    for index, other_wl, sparse in others:
+        other_results.append(side_workload(mv, synth, torch, np, other_wl, index, sparse_edits=sparse))
+        del other_wl
+    others = []
+    copy_rate = device_copy_rate(torch)
+    # the cameras + render protocol (worlds uploaded once): a fixed 100 steps
+    static_result = None
+    if not args.static_worlds and not args.sparse_edits:
+        el2, rm2 = leg.timed(100, 10, static_worlds=True)
+        static_result = {"step": leg.step_name(True), "steps": 100, "warmup": 10, "obs_per_s": n * 100 / el2,
+                         "ms_per_step": el2 * 1e3 / 100, "render_kernel_ms": float(rm2.mean())}
 
-    render_ms = np.array([a.elapsed_time(b) for a, b in events])
+    # ---- headline: W warm-up steps, K timed steps
+    elapsed, render_ms = leg.timed(args.steps, args.warmup, static_worlds=args.static_worlds)
     ms_per_step = elapsed * 1e3 / args.steps
     obs_per_s = n * args.steps / elapsed
     rays_per_obs = H * W
@@ -213,7 +365,7 @@ def main() -> int:
     achieved = alg_bytes / (render_ms.mean() * 1e-3) / 1e9
 
     result = {
-        "metric": "egocentric observations/sec (128\u00d772 RGB+depth) on 1 MI355X; % of HBM peak",
+        "metric": "egocentric observations/sec (128×72 RGB+depth) on 1 MI355X; % of HBM peak",
         "value": obs_per_s,
         "unit": "observations/s",
         "n_gpus": 1,
@@ -227,11 +379,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": spec.name, "num_envs": spec.num_envs, "agents_per_env": spec.agents_per_env,
                    "grid": list(spec.grid), "image": [W, H], "num_materials": spec.num_materials,
-                   "observations_per_step": n, "camera_sets": int(n_sets),
-                   "step": ("render only after one upload" if args.static_worlds else
-                            "mv_update_voxels(device) + mv_set_cameras(device) + mv_render_batch"
-                            if (args.sparse_edits and spec.dynamic) else
-                            "mv_upload_worlds(device) + mv_set_cameras(device) + mv_render_batch")},
+                   "observations_per_step": n, "camera_sets": int(leg.n_sets),
+                   "step": leg.step_name(args.static_worlds)},
         "rays_per_s": obs_per_s * rays_per_obs,
         "render_kernel_ms": {"mean": float(render_ms.mean()), "median": float(np.median(render_ms)),
                              "p95": float(np.percentile(render_ms, 95))},
@@ -239,43 +388,32 @@ def main() -> int:
         "hbm_peak_fraction": achieved / HBM_PEAK_GBS,
         "generator_seconds": gen_s,
         "input_sha256": input_digest(wl),
+        "run_order": "inputs generated and uploaded; cold-start sample; other workloads; device copy; cameras+render "
+                     "protocol (100 steps); headline region; delivery to host; CPU oracle",
+        "cold_start": {"what": "the first 20 steps after the set-up's idle time, no warm-up",
+                       "obs_per_s": n * 20 / cold_el, "ms_per_step": cold_el * 1e3 / 20,
+                       "render_kernel_ms": float(cold_rm.mean())},
     }
-    traffic = measured_traffic(spec.name)
-    mean_steps = ORACLE_MEAN_STEPS.get(args.config)
-    alg_ops = algorithmic_lane_ops_per_ray(mean_steps) * rays_per_obs * n if mean_steps else None
-    if alg_ops is not None:
-        alu_achieved = alg_ops / (render_ms.mean() * 1e-3) / 1e9
-        # plain vector arithmetic binds the render kernel (neither HBM nor LDS comes close, see below)
-        result["roofline"] = {"bound": "alu", "kernel": "mv::render_kernel", "achieved": alu_achieved,
-                              "peak": ALU_PEAK_GOPS, "unit": "G lane-instructions/s",
-                              "frac": alu_achieved / ALU_PEAK_GOPS, "traffic": traffic,
-                              "algorithmic_ops_per_launch": alg_ops, "oracle_mean_steps_per_ray": mean_steps}
-        executed = measured_traffic(spec.name, 3)
-        if executed is not None:
-            # what the kernel really executes (profiled counter), next to the model's count
-            result["roofline"]["executed_ops_per_launch"] = executed
-            result["roofline"]["executed_frac"] = executed / (render_ms.mean() * 1e-3) / 1e9 / ALU_PEAK_GOPS
-    result["hbm_roofline"] = {"bound": "hbm", "kernel": "mv::render_kernel", "achieved": achieved,
-                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                              "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
-                              "device_copy_GBs": device_copy_rate(torch)}
-    lds_bytes = measured_traffic(spec.name, 2)
-    if lds_bytes is not None:
-        # LDS peak: 256 CUs x 128 bytes per clock x 2.4 GHz
-        lds_peak = 256 * 128 * 2.4
-        result["lds_roofline"] = {"bound": "lds", "kernel": "mv::render_kernel",
-                                  "achieved": lds_bytes / (render_ms.mean() * 1e-3) / 1e9, "peak": lds_peak,
-                                  "unit": "GB/s", "frac": lds_bytes / (render_ms.mean() * 1e-3) / 1e9 / lds_peak,
-                                  "bytes_per_launch": lds_bytes}
+    if with_others:
+        result["other_workloads"] = other_results
 
+    if static_result is not None:
+        result["static_worlds_obs_per_s"] = static_result["obs_per_s"]
+        result["static_worlds"] = static_result
+    if not args.no_host_delivery and not spec.dynamic:
+        result["delivered_to_host"] = host_delivery(mv, torch, leg)
+
+    # ---- the oracle on the host cores: bounded sample of the same workload; also the per-ray step count that
+    #      the ALU roofline is priced with
+    mean_steps, steps_source = None, None
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
         cores = min(os.cpu_count() or 1, 16)
         envs = min(args.cpu_sample_envs, spec.num_envs)
+        obs = envs * spec.agents_per_env
         ob = orc.OracleBatch(envs, spec.agents_per_env, spec.grid, W, H, spec.num_materials)
-        ob.upload_worlds(wl.voxels[:envs] if not spec.dynamic else grids[0][:envs], wl.palette[:envs])
-        first_cams = (cams_l[0] if spec.dynamic else cams_np[0])[: envs * spec.agents_per_env]
-        ob.set_cameras(first_cams, None if not spec.dynamic else self_l[0][: envs * spec.agents_per_env])
+        ob.upload_worlds(leg.first_grid[:envs], wl.palette[:envs])
+        ob.set_cameras(leg.first_cams[:obs], None if leg.first_self is None else leg.first_self[:obs])
         # repeat whole passes (the same camera set: the oracle's cost does not depend on which) until the
         # sample amounts to roughly 10 s of CPU work
         passes, cpu_s = 0, 0.0
@@ -284,17 +422,59 @@ def main() -> int:
             ob.render(threads=cores, side_channels=False)
             passes += 1
             cpu_s = time.perf_counter() - t0
-        steps_sample = ob.render(first_obs=0, count=min(64, envs * spec.agents_per_env), threads=cores).steps
+        # one more pass over the same observations for the step counter, in chunks that keep the arrays small
+        total_steps, chunk = 0, 1024
+        for o0 in range(0, obs, chunk):
+            c = min(chunk, obs - o0)
+            total_steps += int(ob.render(first_obs=o0, count=c, threads=cores, side_channels="steps").steps.sum(dtype=np.int64))
+        mean_steps = total_steps / (obs * H * W)
+        steps_source = f"this run's oracle pass over {obs} observations of camera set 0"
         t1 = time.perf_counter()
-        ob.render(first_obs=0, count=min(64, envs * spec.agents_per_env), threads=1, side_channels=False)
-        one_core = min(64, envs * spec.agents_per_env) / (time.perf_counter() - t1)
-        result["cpu_baseline"] = {"value": passes * envs * spec.agents_per_env / cpu_s, "unit": "observations/s",
+        ob.render(first_obs=0, count=min(64, obs), threads=1, side_channels=False)
+        one_core = min(64, obs) / (time.perf_counter() - t1)
+        result["cpu_baseline"] = {"value": passes * obs / cpu_s, "unit": "observations/s",
                                   "cores": cores, "kind": "oracle",
                                   "sample": f"{passes} passes over the first {envs} environments "
-                                            f"({envs * spec.agents_per_env} observations) of camera set 0, "
+                                            f"({obs} observations) of camera set 0, "
                                             f"{cpu_s:.2f} s wall on {cores} threads",
                                   "one_core_value": one_core,
-                                  "mean_dda_steps_per_ray": float(steps_sample.mean())}
+                                  "mean_dda_steps_per_ray": mean_steps}
+    else:
+        mean_steps = committed_mean_steps(spec.name)
+        steps_source = "profiles/oracle_mean_steps.txt" if mean_steps is not None else None
+
+    # ---- rooflines of the render kernel (the dominant kernel), all priced with this run's mean launch time
+    launch_s = render_ms.mean() * 1e-3
+    prof = profiled_counters(spec.name)
+    traffic = prof["hbm_bytes"] if prof else None
+    if mean_steps is not None:
+        alg_ops = algorithmic_lane_ops_per_ray(mean_steps) * rays_per_obs * n
+        alu_achieved = alg_ops / launch_s / 1e9
+        # plain vector arithmetic binds the render kernel (neither HBM nor LDS comes close, see below)
+        result["roofline"] = {"bound": "alu", "kernel": "mv::render_kernel", "achieved": alu_achieved,
+                              "peak": ALU_PEAK_GOPS, "unit": "G lane-instructions/s",
+                              "frac": alu_achieved / ALU_PEAK_GOPS, "traffic": traffic,
+                              "algorithmic_ops_per_launch": alg_ops, "oracle_mean_steps_per_ray": mean_steps,
+                              "mean_steps_source": steps_source}
+        if prof:
+            # what the kernel really executes (profiled counter), next to the model's count
+            result["roofline"]["executed_ops_per_launch"] = prof["valu_lane_ops"]
+            result["roofline"]["executed_frac"] = prof["valu_lane_ops"] / launch_s / 1e9 / ALU_PEAK_GOPS
+    result["hbm_roofline"] = {"bound": "hbm", "kernel": "mv::render_kernel", "achieved": achieved,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                              "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
+                              "device_copy_GBs": copy_rate}
+    if prof:
+        result["lds_roofline"] = {"bound": "lds", "kernel": "mv::render_kernel",
+                                  "achieved": prof["lds_bytes"] / launch_s / 1e9, "peak": LDS_PEAK_GBS,
+                                  "unit": "GB/s", "frac": prof["lds_bytes"] / launch_s / 1e9 / LDS_PEAK_GBS,
+                                  "bytes_per_launch": prof["lds_bytes"]}
+        result["from_profile"] = {"file": "profiles/render_traffic.txt",
+                                  "fields": ["roofline.traffic", "roofline.executed_ops_per_launch",
+                                             "hbm_roofline.traffic", "lds_roofline.bytes_per_launch"],
+                                  "kernel_source_sha256": prof["kernel_source_sha256"]}
+    else:
+        result["from_profile"] = None          # no counter summary for this kernel source: those fields are left out
     print(json.dumps(result))
     return 0
 

@@ -188,15 +188,17 @@ class OracleBatch:
             raise ValueError(f"mvo_set_cameras failed ({rc})")
 
     def render(self, first_obs: int = 0, count: Optional[int] = None, threads: int = 1,
-               side_channels: bool = True) -> Rendered:
+               side_channels=True) -> Rendered:
+        """``side_channels``: True = steps, edge margin and exact t; "steps" = the step counter only; False = none."""
         n = self.N * self.A - first_obs if count is None else count
         H, W = self.H, self.W
+        all_channels = side_channels is True
         out = Rendered(np.empty((n, H, W, 3), np.uint8), np.empty((n, H, W), np.float32),
                        np.empty((n, H, W), np.uint8), np.empty((n, H, W), np.int32),
                        np.empty((n, H, W), np.uint8),
                        np.empty((n, H, W), np.int32) if side_channels else None,
-                       np.empty((n, H, W), np.float64) if side_channels else None,
-                       np.empty((n, H, W), np.float64) if side_channels else None)
+                       np.empty((n, H, W), np.float64) if all_channels else None,
+                       np.empty((n, H, W), np.float64) if all_channels else None)
         rc = _load().mvo_render(self._h, first_obs, n, _ptr(out.rgb), _ptr(out.depth),
                                 _ptr(out.material), _ptr(out.hit_index), _ptr(out.face),
                                 _ptr(out.steps), _ptr(out.edge_margin), _ptr(out.t), threads)
