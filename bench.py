@@ -128,13 +128,13 @@ def device_copy_rate(torch) -> float:
 class Leg:
     """One workload resident on the device: batch object, inputs of a few steps, output tensors."""
 
-    def __init__(self, mv, synth, torch, np, wl, index, sparse_edits=False, tiles_per_block=0):
+    def __init__(self, mv, synth, torch, np, wl, index, sparse_edits=False, tiles_per_block=0, coarse_level=0):
         spec = wl.spec
         dev = torch.device("cuda", 0)
         self.torch, self.np, self.spec, self.wl = torch, np, spec, wl
         self.stream = torch.cuda.current_stream().cuda_stream
         self.batch = mv.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height,
-                              tiles_per_block=tiles_per_block)
+                              tiles_per_block=tiles_per_block, coarse_level=coarse_level)
         self.pal_d = torch.from_numpy(wl.palette).to(dev)
         self.sparse = bool(sparse_edits and spec.dynamic)
         self.edits_d = []
@@ -293,6 +293,8 @@ def main() -> int:
     ap.add_argument("--sparse-edits", action="store_true",
                     help="dynamic workload only: send the changed voxels of each step with mv_update_voxels instead "
                          "of re-uploading whole grids")
+    ap.add_argument("--coarse-level", type=int, default=0,
+                    help="1: render with the optional second occupancy level (same images; measured slower)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the side measurements on the other workloads (profiling runs)")
     ap.add_argument("--no-host-delivery", action="store_true", help="skip the delivery-to-host-memory measurement")
@@ -336,7 +338,8 @@ def main() -> int:
         others = [(c, synth.generate(c), False) for c in (1, 3, 4)]
         others.insert(2, (3, synth.generate(3), True))
         others += [(s.index, synth.generate_extra(name), False) for name, s in synth.EXTRA_SPECS.items()]
-    leg = Leg(mv, synth, torch, np, wl, args.config, sparse_edits=args.sparse_edits, tiles_per_block=args.tiles_per_block)
+    leg = Leg(mv, synth, torch, np, wl, args.config, sparse_edits=args.sparse_edits, tiles_per_block=args.tiles_per_block,
+              coarse_level=args.coarse_level)
     n, H, W = spec.num_obs, spec.height, spec.width
 
     # ---- the first steps after the idle time of the set-up, for the record
@@ -380,7 +383,7 @@ def main() -> int:
         "config": {"workload": spec.name, "num_envs": spec.num_envs, "agents_per_env": spec.agents_per_env,
                    "grid": list(spec.grid), "image": [W, H], "num_materials": spec.num_materials,
                    "observations_per_step": n, "camera_sets": int(leg.n_sets),
-                   "step": leg.step_name(args.static_worlds)},
+                   "step": leg.step_name(args.static_worlds), "coarse_level": args.coarse_level},
         "rays_per_s": obs_per_s * rays_per_obs,
         "render_kernel_ms": {"mean": float(render_ms.mean()), "median": float(np.median(render_ms)),
                              "p95": float(np.percentile(render_ms, 95))},

@@ -74,7 +74,9 @@ typedef struct {
     float   light_dir[3];      /* direction TOWARDS the light, any non-zero length                */
     float   ambient, diffuse;  /* face intensity = ambient + diffuse * max(0, n.L)                */
     uint8_t sky_rgb[3];        /* colour of rays that leave the grid                              */
-    uint8_t reserved0;         /* must be 0                                                       */
+    uint8_t coarse_level;      /* 0 (default) or 1: 1 adds a second, coarser occupancy level (the OR of
+                                  pairs of grid rows) that long rays use to cross empty space in fewer
+                                  steps; results are the same bit for bit; grids up to 64x64 only      */
     int32_t device;            /* HIP device ordinal                                              */
     int32_t tiles_per_block;   /* 0 = choose automatically; otherwise the number of 8x8-pixel
                                   tiles one workgroup renders (a launch-shape knob, results do

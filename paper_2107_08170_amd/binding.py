@@ -31,7 +31,7 @@ class MvConfig(C.Structure):
                 ("width", C.c_int32), ("height", C.c_int32), ("hfov_rad", C.c_float),
                 ("num_materials", C.c_int32), ("light_dir", C.c_float * 3),
                 ("ambient", C.c_float), ("diffuse", C.c_float), ("sky_rgb", C.c_uint8 * 3),
-                ("reserved0", C.c_uint8), ("device", C.c_int32), ("tiles_per_block", C.c_int32)]
+                ("coarse_level", C.c_uint8), ("device", C.c_int32), ("tiles_per_block", C.c_int32)]
 
 
 class MvBar(C.Structure):
@@ -124,7 +124,7 @@ def make_config(num_envs: int, agents_per_env: int, grid: Sequence[int], num_mat
                 width: int = 128, height: int = 72, hfov_rad: Optional[float] = None,
                 light_dir: Optional[Sequence[float]] = None, ambient: Optional[float] = None,
                 diffuse: Optional[float] = None, sky_rgb: Optional[Sequence[int]] = None,
-                device: int = 0, tiles_per_block: int = 0) -> MvConfig:
+                device: int = 0, tiles_per_block: int = 0, coarse_level: int = 0) -> MvConfig:
     """``mv_default_config`` with the given fields filled in."""
     cfg = default_config()
     cfg.num_envs, cfg.agents_per_env = num_envs, agents_per_env
@@ -143,6 +143,7 @@ def make_config(num_envs: int, agents_per_env: int, grid: Sequence[int], num_mat
         cfg.sky_rgb[:] = [int(v) for v in sky_rgb]
     cfg.device = device
     cfg.tiles_per_block = tiles_per_block
+    cfg.coarse_level = coarse_level
     return cfg
 
 
@@ -179,10 +180,10 @@ class Batch:
                  width: int = 128, height: int = 72, hfov_rad: Optional[float] = None,
                  light_dir: Optional[Sequence[float]] = None, ambient: Optional[float] = None,
                  diffuse: Optional[float] = None, sky_rgb: Optional[Sequence[int]] = None,
-                 device: int = 0, tiles_per_block: int = 0):
+                 device: int = 0, tiles_per_block: int = 0, coarse_level: int = 0):
         lib = load_library()
         cfg = make_config(num_envs, agents_per_env, grid, num_materials, width, height, hfov_rad, light_dir, ambient,
-                          diffuse, sky_rgb, device, tiles_per_block)
+                          diffuse, sky_rgb, device, tiles_per_block, coarse_level)
         self.cfg = cfg
         self._h = C.c_void_p()
         _check(lib.mv_create_batch(C.byref(cfg), C.byref(self._h)))

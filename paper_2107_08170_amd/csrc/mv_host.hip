@@ -117,7 +117,7 @@ static int check_config(const mv_config* cfg, const char* who, mv::GridLayout* l
         return fail(MV_ERR_ARG, "%s: hfov_rad must lie in (0, pi)", who);
     if (cfg->num_materials < 1 || cfg->num_materials > 255)
         return fail(MV_ERR_ARG, "%s: num_materials must be in 1..255", who);
-    if (cfg->reserved0 != 0) return fail(MV_ERR_ARG, "%s: reserved0 must be 0", who);
+    if (cfg->coarse_level > 1) return fail(MV_ERR_ARG, "%s: coarse_level must be 0 or 1", who);
     if (cfg->tiles_per_block < 0) return fail(MV_ERR_ARG, "%s: tiles_per_block must be >= 0", who);
     if (cfg->device < 0) return fail(MV_ERR_ARG, "%s: device must be >= 0", who);
     const double lx = cfg->light_dir[0], ly = cfg->light_dir[1], lz = cfg->light_dir[2];
@@ -131,7 +131,8 @@ static int check_config(const mv_config* cfg, const char* who, mv::GridLayout* l
     const long long num_obs = (long long)cfg->num_envs * cfg->agents_per_env;
     if (num_obs > (1ll << 24)) return fail(MV_ERR_ARG, "%s: more than 2^24 observations", who);
     const mv::GridLayout layout = mv::make_layout(cfg->grid_x, cfg->grid_y, cfg->grid_z);
-    const mv::LdsPlan plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1, cfg->grid_z);
+    const mv::LdsPlan plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1, cfg->grid_z,
+                                          cfg->coarse_level != 0);
     if (plan.bytes == 0)
         return fail(MV_ERR_CAPACITY, "%s: the occupancy bit rows of one %dx%dx%d grid do not fit in %zu bytes of LDS", who,
                     cfg->grid_x, cfg->grid_y, cfg->grid_z, mv::kLdsBudget);
@@ -475,10 +476,12 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
             if (seen > 1 && seen < staged) staged = seen;
         }
     }
-    const mv::LdsPlan plan = mv::plan_lds(b->layout, b->cfg.width, b->cfg.height, b->materials_plus_one, staged);
+    const mv::LdsPlan plan = mv::plan_lds(b->layout, b->cfg.width, b->cfg.height, b->materials_plus_one, staged,
+                                          b->cfg.coarse_level != 0);
 
     mv::RenderParams p{};
     p.staged_layers = staged;
+    p.coarse_after = b->cfg.coarse_level != 0 ? mv::kCoarseAfterTurns : -1;
     p.heights = mv::HeightFeedback{ b->d_height, b->h_height_dev };
     p.active = b->all_active ? nullptr : b->d_active;
     p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
@@ -746,6 +749,7 @@ extern "C" int mv_render_worlds_noalloc(const mv_config* cfg, const uint8_t* vox
 
     mv::RenderParams p{};
     p.staged_layers = cfg->grid_z;            // no height feedback without a batch object: stage every layer
+    p.coarse_after = cfg->coarse_level != 0 ? mv::kCoarseAfterTurns : -1;
     p.heights = no_feedback;
     p.active = nullptr;
     p.bits = d_bits; p.ztop = d_ztop; p.vox = voxels; p.lut = d_lut; p.rec = d_rec; p.sx = d_sx; p.sy = d_sy;

@@ -20,6 +20,7 @@ constexpr int kTile = 8;                  // a wave renders an 8x8 pixel tile
 constexpr int kXcds = 8;                  // MI355X: 8 XCDs, workgroups are dealt round-robin
 constexpr int kNumFaces = 7;              // six faces + "inside"
 constexpr size_t kLdsBudget = 160 * 1024; // LDS one workgroup may use on gfx950
+constexpr int kCoarseAfterTurns = 5;       // coarse level: ordinary turns of a ray before it starts looking at pairs of rows
 constexpr size_t kPackStaticLds = 1024;   // room kept for the pack kernel's static LDS words next to its dynamic share
 
 // Occupancy bits in device memory, per environment ("bit rows"):
@@ -74,6 +75,7 @@ struct RenderParams {
     int32_t max_steps;
     int32_t threads;                      // workgroup size (multiple of 64)
     int32_t staged_layers;                // row-scan grids: layers 0 .. staged_layers-1 of the bit rows go to LDS
+    int32_t coarse_after;                 // < 0: no coarse level; else the ordinary turns a ray makes before it uses it
     HeightFeedback heights;
 };
 
@@ -84,8 +86,9 @@ struct LdsPlan {
     size_t bytes;         // dynamic LDS per workgroup
     int    threads;       // workgroup size that keeps a CU busy with that much LDS
 };
-// staged_layers: how many z layers of a row-scan grid the workgroup keeps in LDS (1..Z; ignored for other grids)
-LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers);
+// staged_layers: how many z layers of a row-scan grid the workgroup keeps in LDS (1..Z; ignored for other grids);
+// coarse: with the pair-of-rows arrays of the optional coarse level
+LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers, bool coarse);
 
 // Launchers (mv_kernels.hip).  All enqueue on `stream` and return hipGetLastError().
 hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t stream);

@@ -43,13 +43,13 @@ static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 // LDS map (bytes):  [16 scan-class records, 128 B apart] | [sx: W floats][sy: H floats] |
 //                   [colour table 7*(M+1) dwords] | bit rows
 // fast grids stage four row arrays (x, x mirrored, y, y mirrored) of `staged_layers` layers each; others stage
-// all x rows.
+// all x rows.  With the coarse level, four more arrays follow: the OR of each pair of neighbouring rows of a layer.
 struct LdsMap {
     uint32_t scalars, classes, lut, rows;
     uint32_t total;
 };
 
-static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers)
+static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers, bool coarse)
 {
     LdsMap m{};
     size_t off = 0;
@@ -59,14 +59,15 @@ static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one,
     off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
     m.rows = (uint32_t)off;
     off += g.fast ? 16 * (size_t)staged_layers * (size_t)(g.X + g.Y) : (size_t)g.xrow_words * 8;
+    if (g.fast && coarse) off += 16 * (size_t)staged_layers * (size_t)((g.X + 1) / 2 + (g.Y + 1) / 2);
     m.total = (uint32_t)off;
     return m;
 }
 
-LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers)
+LdsPlan plan_lds(const GridLayout& g, int W, int H, int materials_plus_one, int staged_layers, bool coarse)
 {
     LdsPlan plan{};
-    const LdsMap m = lds_map(g, W, H, materials_plus_one, staged_layers);
+    const LdsMap m = lds_map(g, W, H, materials_plus_one, staged_layers, coarse);
     if (m.total > kLdsBudget) return plan;                                  // bytes == 0: does not fit
     plan.bytes = m.total;
     // as many waves per workgroup as fill the CU's wave slots with the workgroups its LDS can hold
@@ -527,6 +528,16 @@ struct alignas(16) ScanClass {
 };
 static_assert(sizeof(ScanClass) == 80, "scan class record must be 80 bytes");
 
+// Coarse level (optional): the OR of each pair of neighbouring rows (2J, 2J+1) of a layer, one array per row
+// array.  These constants of a scan class sit behind its record, in the same 128-byte slot.
+struct alignas(16) PairClass {
+    int addr0;          // LDS byte address of the camera's pair row in this class's pair array
+    int sv;             // pair-address step when the ray crosses from one pair into the next: +-8 bytes
+    int sz;             // pair-address step per z crossing: +-8 * (pairs per layer)
+    int inner0;         // 1 if the first v plane ahead of the camera lies inside its pair, 0 if it bounds it
+};
+static_assert(sizeof(ScanClass) + sizeof(PairClass) <= kClassStride, "class slot too small");
+
 // Plain 3D-DDA through the x rows (any row width), in LDS or in global memory.  Used for grids wider than 64
 // voxels, for cameras outside the grid, and for workgroups whose world is taller than the layers staged.  Crossing parameters are t = n*|1/d| + t_first (one fused op, error relative
 // to t itself) rather than accumulated.
@@ -690,8 +701,8 @@ __device__ __forceinline__ int mad24s(int a, int b_uniform, int c)
 // t_end, which puts the last cell of the run at U at most (U only through rounding at the far boundary);
 // with U <= 63 that still is a valid bit position of an always-empty cell, and the clamp to U - 1 that
 // 64-cell rows need is left out.
-template <bool kNarrow>
-__device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz)
+template <bool kNarrow, bool kCoarse>
+__device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz, int fine_turns)
 {
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
@@ -737,8 +748,81 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     // shifter ignores the upper bits.  Nothing after the loop needs i_from: the hit cell follows from
     // the lowest set bit of in_range and i_to, and bit 0 of r tells whether it is the row's entry cell.
     // The next row is requested as soon as its address is known, at the end of the turn before (render -1 %).
-    uint64_t row = *(lds_u64_ptr)(uintptr_t)addr;
+    uint64_t row = 0;
+    if constexpr (!kCoarse) row = *(lds_u64_ptr)(uintptr_t)addr;
     int i_a = c.i0, i_b;
+    if constexpr (kCoarse) {
+        // Coarse level: after `fine_turns` ordinary turns a ray first looks at the PAIR of rows it is in (the OR of
+        // rows 2J and 2J+1 of its layer), over the whole run of cells it covers before it leaves the pair or the
+        // layer.  An empty run takes it there in one turn (one or two v crossings, or one v crossing and the z
+        // crossing, with the very comparisons the ordinary turns would make, so the state it arrives in is the
+        // state they would arrive in); otherwise it takes one ordinary turn.  Every decision uses the same
+        // crossing parameters as the ordinary scan: the result is the same bit for bit.
+        PairClass pc;
+        *reinterpret_cast<u32x4*>(&pc) = *(lds_u32x4_ptr)(uintptr_t)(classes_addr + qoff + (uint32_t)sizeof(ScanClass));
+        t_v = t0_v; t_z = t0_z;
+        uint32_t addr_p = (uint32_t)pc.addr0;
+        int inner = pc.inner0;                  // the next v plane lies inside the current pair
+        int i_from = i_a;
+        r = 0; in_range = 0; i_last = i_from;
+        for (int turn = 0;; ++turn) {
+            if (turn >= fine_turns) {
+                const float t_pair = inner ? fmaf(n_v + 1.0f, dt_v, t0_v) : t_v;     // where the ray leaves the pair along v
+                const float t_out = kNarrow ? vmin3(t_pair, t_z, t_end) : vmin(t_pair, t_z);
+                const float u_out = fmaf(t_out, dua, c.Pu);
+                const int i_to = kNarrow ? (int)u_out : min((int)u_out, c.um1);
+                const uint64_t pair_row = *(lds_u64_ptr)(uintptr_t)addr_p;
+                const uint64_t pr = pair_row >> i_from;
+                const uint64_t pin = pr << ((((i_to) ^ -1) + (i_from)) & 63);
+                if (pin == 0) {
+                    if (!(t_out < t_end)) { r = pr; in_range = 0; i_last = i_to; break; }   // leaves the grid: a miss
+                    if (t_pair <= t_z) {
+                        // out of the pair along v: the plane inside it (if it was still ahead) and the one behind it
+                        n_v += inner ? 2.0f : 1.0f;
+                        addr += (uint32_t)(inner ? 2 * c.sv : c.sv);
+                        addr_p += (uint32_t)pc.sv;
+                        inner = 1;
+                    } else {
+                        // the z crossing comes first; the plane inside the pair may still come before it
+                        const bool mid = inner && t_v <= t_z;
+                        n_v += mid ? 1.0f : 0.0f;
+                        addr += (uint32_t)(mid ? c.sv : 0);
+                        inner = mid ? 0 : inner;
+                        n_z += 1.0f;
+                        addr += (uint32_t)c.sz;
+                        addr_p += (uint32_t)pc.sz;
+                    }
+                    t_v = fmaf(n_v, dt_v, t0_v);
+                    t_z = fmaf(n_z, dt_z, t0_z);
+                    i_from = i_to;
+                    continue;
+                }
+            }
+            // an ordinary turn on the row the ray is in
+            const uint64_t fine_row = *(lds_u64_ptr)(uintptr_t)addr;
+            const float t_out = kNarrow ? vmin3(t_v, t_z, t_end) : vmin(t_v, t_z);
+            const float u_out = fmaf(t_out, dua, c.Pu);
+            const int i_to = kNarrow ? (int)u_out : min((int)u_out, c.um1);
+            r = fine_row >> i_from;
+            in_range = r << ((((i_to) ^ -1) + (i_from)) & 63);
+            i_last = i_to;
+            if ((in_range != 0) | !(t_out < t_end)) break;
+            const bool cv = t_v <= t_z;
+            if (cv) {
+                n_v += 1.0f;
+                addr += (uint32_t)c.sv;
+                if (!inner) addr_p += (uint32_t)pc.sv;      // that plane bounded the pair
+                inner ^= 1;
+            } else {
+                n_z += 1.0f;
+                addr += (uint32_t)c.sz;
+                addr_p += (uint32_t)pc.sz;
+            }
+            t_v = fmaf(n_v, dt_v, t0_v);
+            t_z = fmaf(n_z, dt_z, t0_z);
+            i_from = i_to;
+        }
+    } else
     // The loop in assembly: the compiler's structured control flow spends about ten scalar instructions per turn
     // on lane masks (two breaks per trip); written out, a turn needs two.  Lanes that are done simply leave
     // the execution mask (it only ever shrinks; restored after the loop), so every register of a finished lane
@@ -870,7 +954,8 @@ __device__ __forceinline__ uint32_t next_in_quad(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xF9, 0xF, 0xF, false);
 }
 
-template <bool AUX, bool PACKED, bool FAST>
+// COARSE: with the optional second occupancy level (pairs of rows), row-scan grids only
+template <bool AUX, bool PACKED, bool FAST, bool COARSE = false>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void render_kernel(RenderParams p)
 {
     extern __shared__ __align__(16) uint8_t lds[];
@@ -1035,6 +1120,10 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             }
         }
     }
+    // pair arrays (coarse level): [x pairs][x pairs mirrored][y pairs][y pairs mirrored] behind the row arrays
+    const int vpx = (Y + 1) / 2, vpy = (X + 1) / 2;         // pairs per layer of the x / y arrays
+    const int pxw = staged * vpx, pyw = staged * vpy;
+    const uint32_t off_pairs = off_rows + 16u * (uint32_t)(sxw + syw);
     if (use_rows && threadIdx.x >= 64 && threadIdx.x < 64 + kScanClasses) {
         const int q = threadIdx.x - 64;
         const bool xmaj = q < 8, neg = q & 4, vneg = q & 2, zneg = q & 1;
@@ -1078,8 +1167,43 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         c.stride_z = (float)(zneg ? -X * Y : X * Y);
         c.idx0 = (float)(kc * X * Y + j0 * sv_idx + (neg ? (U - 1) * su : 0));
         *reinterpret_cast<ScanClass*>(lds + off_classes + q * kClassStride) = c;
+        if (COARSE) {
+            const int VP = xmaj ? vpx : vpy;
+            PairClass pc;
+            const uint32_t pair_off = off_pairs + 8u * (uint32_t)(xmaj ? (neg ? pxw : 0) : 2 * pxw + (neg ? pyw : 0));
+            pc.addr0 = (int)(lds_base + pair_off + 8u * (uint32_t)(kc * VP + (j0 >> 1)));
+            pc.sv = vneg ? -8 : 8;
+            pc.sz = zneg ? -8 * VP : 8 * VP;
+            // rising v: the plane above cell j0 lies inside its pair if j0 is even; falling v: the plane below it if j0 is odd
+            pc.inner0 = ((j0 & 1) == (vneg ? 1 : 0)) ? 1 : 0;
+            *reinterpret_cast<PairClass*>(lds + off_classes + q * kClassStride + sizeof(ScanClass)) = pc;
+        }
     }
     __syncthreads();
+
+    if (COARSE && use_rows) {
+        const uint64_t* ax = lds_rows;
+        const uint64_t* axm = ax + sxw;
+        const uint64_t* ay = axm + sxw;
+        const uint64_t* aym = ay + syw;
+        uint64_t* px = reinterpret_cast<uint64_t*>(lds + off_pairs);
+        uint64_t* pxm = px + pxw;
+        uint64_t* py = pxm + pxw;
+        uint64_t* pym = py + pyw;
+        for (int w = threadIdx.x; w < pxw; w += threads) {
+            const int k = w / vpx, J = w - k * vpx, a = k * Y + 2 * J;
+            const bool two = 2 * J + 1 < Y;
+            px[w] = ax[a] | (two ? ax[a + 1] : 0ull);
+            pxm[w] = axm[a] | (two ? axm[a + 1] : 0ull);
+        }
+        for (int w = threadIdx.x; w < pyw; w += threads) {
+            const int k = w / vpy, J = w - k * vpy, a = k * X + 2 * J;
+            const bool two = 2 * J + 1 < X;
+            py[w] = ay[a] | (two ? ay[a + 1] : 0ull);
+            pym[w] = aym[a] | (two ? aym[a + 1] : 0ull);
+        }
+        __syncthreads();
+    }
 
     // A camera inside a solid voxel (its own body is already gone) sees that voxel everywhere, at depth 0
     // with the "inside" face: one test per workgroup instead of one per ray.
@@ -1192,7 +1316,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             // a5: traversal
             Hit h;
             if (kRowsOnly) {
-                h = trace_rows<kNarrow>(lds_base + off_classes, d[0], d[1], d[2]);
+                h = trace_rows<kNarrow, COARSE>(lds_base + off_classes, d[0], d[1], d[2], p.coarse_after);
             } else if (use_rows) {
                 h.idx = cam_idx; h.face = 6; h.t = 0.0f;
             } else if (FAST) {
@@ -1267,10 +1391,10 @@ hipError_t launch_active_from_done(const uint8_t* done, uint8_t* active, int n, 
     return hipGetLastError();
 }
 
-template <bool AUX, bool PACKED, bool FAST>
+template <bool AUX, bool PACKED, bool FAST, bool COARSE = false>
 static hipError_t set_lds_limit()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<AUX, PACKED, FAST>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<AUX, PACKED, FAST, COARSE>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
 }
 
@@ -1289,6 +1413,9 @@ hipError_t prepare_kernels()
 #define MV_SET(A, P, F) if (e == hipSuccess) e = set_lds_limit<A, P, F>()
     MV_SET(false, false, false); MV_SET(false, false, true); MV_SET(false, true, false); MV_SET(false, true, true);
     MV_SET(true, false, false);  MV_SET(true, false, true);  MV_SET(true, true, false);  MV_SET(true, true, true);
+#undef MV_SET
+#define MV_SET(A, P) if (e == hipSuccess) e = set_lds_limit<A, P, true, true>()
+    MV_SET(false, false); MV_SET(false, true); MV_SET(true, false); MV_SET(true, true);
 #undef MV_SET
     // the pack kernel also has a few static words of LDS: its dynamic share must leave room for them
     const int pack_limit = (int)(kLdsBudget - kPackStaticLds);
@@ -1310,13 +1437,18 @@ hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t st
     const bool fast = p.g.fast != 0;
     dim3 grid(p.blocks_per_xcd * kXcds), block(p.threads);
 #define MV_LAUNCH(A, P, F) hipLaunchKernelGGL((render_kernel<A, P, F>), grid, block, lds_bytes, stream, p)
-    if (aux) {
+#define MV_LAUNCH_COARSE(A, P) hipLaunchKernelGGL((render_kernel<A, P, true, true>), grid, block, lds_bytes, stream, p)
+    if (fast && p.coarse_after >= 0) {
+        if (aux) { if (packed) MV_LAUNCH_COARSE(true, true); else MV_LAUNCH_COARSE(true, false); }
+        else     { if (packed) MV_LAUNCH_COARSE(false, true); else MV_LAUNCH_COARSE(false, false); }
+    } else if (aux) {
         if (packed) { if (fast) MV_LAUNCH(true, true, true); else MV_LAUNCH(true, true, false); }
         else        { if (fast) MV_LAUNCH(true, false, true); else MV_LAUNCH(true, false, false); }
     } else {
         if (packed) { if (fast) MV_LAUNCH(false, true, true); else MV_LAUNCH(false, true, false); }
         else        { if (fast) MV_LAUNCH(false, false, true); else MV_LAUNCH(false, false, false); }
     }
+#undef MV_LAUNCH_COARSE
 #undef MV_LAUNCH
     return hipGetLastError();
 }

@@ -57,7 +57,7 @@ def test_config_struct_layout_matches_header(lib):
 
 @pytest.mark.parametrize("field,value", [
     ("num_envs", 0), ("agents_per_env", -1), ("grid_x", 0), ("grid_z", -3), ("width", 0), ("height", 20000),
-    ("hfov_rad", 0.0), ("hfov_rad", 3.2), ("num_materials", 0), ("num_materials", 256), ("reserved0", 1),
+    ("hfov_rad", 0.0), ("hfov_rad", 3.2), ("num_materials", 0), ("num_materials", 256), ("coarse_level", 2),
     ("tiles_per_block", -1), ("device", -1), ("ambient", float("nan")),
 ])
 def test_create_rejects_bad_config_before_any_gpu_call(lib, field, value):
