@@ -88,7 +88,7 @@ def profiled_counters(workload: str):
 
 def committed_mean_steps(workload: str):
     """Mean per-cell DDA steps per ray of the CPU oracle on camera set 0, from the committed summary written by
-    ``python -m oracle.mean_steps`` (used only when this run skips its own oracle pass)."""
+    ``python -m tests.oracle_mean_steps`` (used only when this run skips its own oracle pass)."""
     try:
         with open(STEPS_PROFILE) as f:
             for ln in f:

@@ -3,7 +3,7 @@ set 0 of each benchmark workload (the S of the ALU roofline's "10*S + 60" lane-i
 the oracle and the seeded input generators.  The benchmark measures the same figure in its own oracle pass and
 reads this file only when that pass is skipped.
 
-    python -m oracle.mean_steps [max_envs]
+    python -m tests.oracle_mean_steps [max_envs]
 """
 import os
 import sys
@@ -36,7 +36,7 @@ def mean_steps(index: int, max_envs: int) -> tuple:
 def main() -> int:
     max_envs = int(sys.argv[1]) if len(sys.argv) > 1 else 4096
     lines = ["# Mean per-cell DDA steps per ray of the CPU oracle, camera set 0 of each workload.",
-             f"# Written by: python -m oracle.mean_steps {max_envs}   (first <= {max_envs} environments of each workload)",
+             f"# Written by: python -m tests.oracle_mean_steps {max_envs}   (first <= {max_envs} environments of each workload)",
              "# workload  mean_steps_per_ray  environments  observations"]
     for index in (1, 2, 3, 4):
         name, mean, envs, obs = mean_steps(index, max_envs)
