@@ -43,7 +43,7 @@ constexpr int kClassStride = 112;
 
 static size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 
-// LDS map (bytes):  [16 scan-class records, 112 B apart] | [sx: W floats][sy: H floats] |
+// LDS map (bytes):  [16 scan-class records, 112 B apart] | [sx: W floats][one RowRecord per image row] |
 //                   [colour table 7*(M+1) dwords] | bit rows
 // fast grids stage four row arrays (x, x mirrored, y, y mirrored) of `staged_layers` layers each; others stage
 // all x rows.  With the coarse level, four more arrays follow: the OR of each pair of neighbouring rows of a layer.
@@ -57,7 +57,7 @@ static LdsMap lds_map(const GridLayout& g, int W, int H, int materials_plus_one,
     LdsMap m{};
     size_t off = 0;
     m.classes = (uint32_t)off; off += kScanClasses * kClassStride;
-    m.scalars = (uint32_t)off; off = align16(off + (size_t)(W + H) * 4);
+    m.scalars = (uint32_t)off; off = align16(off + (size_t)W * 4) + (size_t)H * 16;      // sx[W], then a 16-byte record per image row
     m.lut = (uint32_t)off;
     off = align16(off + (size_t)kNumFaces * materials_plus_one * 4);
     m.rows = (uint32_t)off;
@@ -531,6 +531,17 @@ struct alignas(16) ScanClass {
 };
 static_assert(sizeof(ScanClass) == 80, "scan class record must be 80 bytes");
 
+// What all pixels of one image row share.  The camera has no roll, so its right axis is horizontal and the vertical
+// component of a pixel ray, d_z = F_z + sy*U_z, depends on the row alone: its clamped reciprocal, the parameter of
+// the first z crossing and the parameter at which the ray leaves the grid along z are computed once per row when a
+// workgroup starts, with the operations a ray would use, instead of once per ray.
+struct alignas(16) RowRecord {
+    float sy;           // pixel-centre scalar of the row, (H - 2r - 1) / H
+    float rcp_z;        // 1 / d_z clamped to +-kBig; its sign is the ray's vertical direction (-0 counts as rising)
+    float t0_z;         // parameter of the first z crossing: distance to the first z plane times |1 / d_z|
+    float tend_z;       // parameter of the crossing that takes the ray out of the (cut) grid along z
+};
+
 // Coarse level (optional): the OR of each pair of neighbouring rows (2J, 2J+1) of a layer, one array per row
 // array.  These constants of a scan class sit behind its record, in the same 128-byte slot.
 struct alignas(16) PairClass {
@@ -705,7 +716,7 @@ __device__ __forceinline__ int mad24s(int a, int b_uniform, int c)
 // with U <= 63 that still is a valid bit position of an always-empty cell, and the clamp to U - 1 that
 // 64-cell rows need is left out.
 template <bool kNarrow, bool kCoarse>
-__device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, float dz, int fine_turns)
+__device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float dy, const RowRecord& rr, int fine_turns)
 {
     const bool xm = fabsf(dx) >= fabsf(dy);
     const float du = xm ? dx : dy;
@@ -717,7 +728,7 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
     uint32_t q = xm ? 0u : 1u;
     q = __builtin_amdgcn_alignbit(q, __float_as_uint(du), 31);
     q = __builtin_amdgcn_alignbit(q, __float_as_uint(dv + 0.0f), 31);
-    q = __builtin_amdgcn_alignbit(q, __float_as_uint(dz + 0.0f), 31);
+    q = __builtin_amdgcn_alignbit(q, __float_as_uint(rr.rcp_z), 31);        // the sign of 1/d_z is the sign of d_z
     const uint32_t qoff = q * (uint32_t)kClassStride;
     ScanClass c;
     {
@@ -728,13 +739,14 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 
     const float dua = fabsf(du);
     const float inv_u = safe_rcp(dua);
-    const float rcp_v = safe_rcp(dv), rcp_z = safe_rcp(dz);
+    const float rcp_v = safe_rcp(dv), rcp_z = rr.rcp_z;
     const float dt_v = fabsf(rcp_v), dt_z = fabsf(rcp_z);
-    // first crossing on an axis: the distance to the first plane in the ray's direction times |1/d|
+    // first crossing on an axis: the distance to the first plane in the ray's direction times |1/d| (along z: from
+    // the image row's record, see RowRecord)
     const float t0_v = c.dist_v * dt_v;
-    const float t0_z = c.dist_z * dt_z;
+    const float t0_z = rr.t0_z;
     // leaving the grid: same n*dt + t0 expression as the crossings, so the comparison below is exact
-    const float t_end = vmin3(c.uexit * inv_u, fmaf(c.nv_max, dt_v, t0_v), fmaf(c.nz_max, dt_z, t0_z));
+    const float t_end = vmin3(c.uexit * inv_u, fmaf(c.nv_max, dt_v, t0_v), rr.tend_z);
 
     // crossings made so far along v and z (without sign; the directions sit in the class), and the parameters
     // of the next ones: t_v = n_v*dt_v + t0_v, t_z likewise
@@ -1005,10 +1017,11 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     // LDS map, mirrors lds_map() on the host
     const uint32_t off_classes = 0;
     const uint32_t off_scalars = kScanClasses * kClassStride;
-    const uint32_t off_lut = off_scalars + (uint32_t)(((p.W + p.H) * 4 + 15) & ~15);
+    const uint32_t off_rowrec = off_scalars + (uint32_t)((p.W * 4 + 15) & ~15);
+    const uint32_t off_lut = off_rowrec + (uint32_t)p.H * 16u;
     const uint32_t off_rows = off_lut + (uint32_t)((kNumFaces * p.materials_plus_one * 4 + 15) & ~15);
     float* lds_sx = reinterpret_cast<float*>(lds + off_scalars);
-    float* lds_sy = lds_sx + p.W;
+    RowRecord* lds_rowrec = reinterpret_cast<RowRecord*>(lds + off_rowrec);
     uint64_t* lds_rows = reinterpret_cast<uint64_t*>(lds + off_rows);
 
     // the camera: uniform for the whole workgroup, read once
@@ -1085,10 +1098,24 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             for (int w = tid; w < g.xrow_words; w += threads) lds_rows[w] = gb[w];
         }
         if (tid < p.W) lds_sx[tid] = first_sx;
-        if (tid < p.H) lds_sy[tid] = first_sy;
+        // image row records (see RowRecord); the z constants are those of the two vertical scan directions
+        auto row_record = [&](float sy) {
+            RowRecord rr;
+            rr.sy = sy;
+            const float dz = fmaf(sy, Uz, fmaf(first_sx, Rz, Fz));      // R_z = 0: the same for every column
+            const bool zneg = (dz + 0.0f) < 0.0f;
+            rr.rcp_z = safe_rcp(dz + 0.0f);
+            const float dt_z = fabsf(rr.rcp_z);
+            const float dist_z = fabsf((float)(zneg ? kc : k0 + 1) - P[2]);
+            const float nz_max = (float)(zneg ? kc : zlim - 1 - kc);
+            rr.t0_z = dist_z * dt_z;
+            rr.tend_z = fmaf(nz_max, dt_z, rr.t0_z);
+            return rr;
+        };
+        if (tid < p.H) lds_rowrec[tid] = row_record(first_sy);
         if (tid < lut_n) ll[tid] = first_lut;
         for (int i = tid + threads; i < p.W; i += threads) lds_sx[i] = p.sx[i];
-        for (int i = tid + threads; i < p.H; i += threads) lds_sy[i] = p.sy[i];
+        for (int i = tid + threads; i < p.H; i += threads) lds_rowrec[i] = row_record(p.sy[i]);
         for (int i = tid + threads; i < lut_n; i += threads) ll[i] = gl[i];
     }
     // This workgroup's copy of the rows is private to one camera: the camera's own body is removed from it
@@ -1223,7 +1250,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const int lx = lane & 7, ly = lane >> 3, quad = lane & 3;
     const int lane_pix = ly * p.W + lx;
     const float* sx_lane = lds_sx + lx;
-    const float* sy_lane = lds_sy + ly;
+    const RowRecord* rowrec_lane = lds_rowrec + ly;
     const int tile_begin = part * tiles_per_block;
     const int tile_end = min(tile_begin + tiles_per_block, p.tiles_per_obs);
     // per-observation bases: everything inside one observation is addressed with 32-bit offsets
@@ -1295,31 +1322,33 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             // PACKED launches have W and H multiples of the tile size: every lane owns a pixel, and its
             // addresses are a per-lane constant plus a per-tile (wave-uniform) offset
             bool active = true;
-            float sx, sy;
+            float sx;
+            RowRecord rr;
             uint32_t pix;
             if (PACKED) {
                 sx = sx_lane[tx * kTile];
-                sy = sy_lane[ty * kTile];
+                rr = rowrec_lane[ty * kTile];
                 pix = (uint32_t)(lane_pix + (ty * p.W + tx) * kTile);
             } else {
                 const int col = tx * kTile + lx, row = ty * kTile + ly;
                 active = col < p.W && row < p.H;
                 const int ccol = min(col, p.W - 1), crow = min(row, p.H - 1);
                 sx = lds_sx[ccol];
-                sy = lds_sy[crow];
+                rr = lds_rowrec[crow];
                 pix = (uint32_t)mad24s(crow, p.W, ccol);
             }
 
-            // a4: ray through the pixel centre, two fused multiply-adds per axis
+            // a4: ray through the pixel centre, two fused multiply-adds per axis (the row scan takes what it needs of
+            // the vertical component from the row record)
             float d[3];
-            d[0] = fmaf(sy, Ux, fmaf(sx, Rx, Fx));
-            d[1] = fmaf(sy, Uy, fmaf(sx, Ry, Fy));
-            d[2] = fmaf(sy, Uz, fmaf(sx, Rz, Fz));
+            d[0] = fmaf(rr.sy, Ux, fmaf(sx, Rx, Fx));
+            d[1] = fmaf(rr.sy, Uy, fmaf(sx, Ry, Fy));
+            if (!kRowsOnly) d[2] = fmaf(rr.sy, Uz, fmaf(sx, Rz, Fz));
 
             // a5: traversal
             Hit h;
             if (kRowsOnly) {
-                h = trace_rows<kNarrow, COARSE>(lds_base + off_classes, d[0], d[1], d[2], p.coarse_after);
+                h = trace_rows<kNarrow, COARSE>(lds_base + off_classes, d[0], d[1], rr, p.coarse_after);
             } else if (use_rows) {
                 h.idx = cam_idx; h.face = 6; h.t = 0.0f;
             } else if (FAST) {
