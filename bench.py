@@ -128,7 +128,8 @@ def device_copy_rate(torch) -> float:
 class Leg:
     """One workload resident on the device: batch object, inputs of a few steps, output tensors."""
 
-    def __init__(self, mv, synth, torch, np, wl, index, sparse_edits=False, tiles_per_block=0, coarse_level=0):
+    def __init__(self, mv, synth, torch, np, wl, index, sparse_edits=False, tiles_per_block=0, coarse_level=0,
+                 object_moves=False):
         spec = wl.spec
         dev = torch.device("cuda", 0)
         self.torch, self.np, self.spec, self.wl = torch, np, spec, wl
@@ -137,17 +138,24 @@ class Leg:
                               tiles_per_block=tiles_per_block, coarse_level=coarse_level)
         self.pal_d = torch.from_numpy(wl.palette).to(dev)
         self.sparse = bool(sparse_edits and spec.dynamic)
-        self.edits_d = []
+        self.moves = bool(object_moves and spec.dynamic)
+        self.edits_d, self.moves_d = [], []
         if spec.dynamic:
             # dynamic worlds: pre-compute the grids/cameras of a few steps on the host, keep them resident
             grids, cams_l, self_l = [wl.voxels], [wl.cameras[0]], [wl.self_voxel[0]]
+            where = [synth.dynamic_positions(wl)]
             for _ in range(3):
                 g, c, s = synth.dynamic_step(wl)
                 grids.append(g); cams_l.append(c); self_l.append(s)
+                where.append(synth.dynamic_positions(wl))
             self.grids_d = [torch.from_numpy(g).to(dev) for g in grids]
             self.cams_d = torch.from_numpy(np.stack(cams_l)).to(dev)
             self.self_d = torch.from_numpy(np.stack(self_l)).to(dev)
             self.first_grid, self.first_cams, self.first_self = grids[0], cams_l[0], self_l[0]
+            if self.moves:                    # the objects' cells at step k-1 and at step k (cyclically)
+                for k in range(len(grids)):
+                    self.moves_d.append(tuple(torch.from_numpy(a).to(dev)
+                                              for a in synth.object_moves(wl, where[k - 1], where[k])))
             if self.sparse:                   # edits that turn grid k-1 into grid k (cyclically)
                 for k in range(len(grids)):
                     e, i, m = synth.grid_edits(grids[k - 1], grids[k])
@@ -176,7 +184,9 @@ class Leg:
     def step(self, i, ev=None, static_worlds=False, rgb=None, depth=None, stream=None):
         stream = self.stream if stream is None else stream
         k = i % self.n_sets
-        if self.sparse and i > 0:
+        if self.moves and i > 0:
+            self.batch.move_voxels(*self.moves_d[k], stream=stream)
+        elif self.sparse and i > 0:
             self.batch.update_voxels(*self.edits_d[k], stream=stream)
         elif not static_worlds or i == 0:
             self.batch.upload_worlds(self.grids_d[k % len(self.grids_d)], self.pal_d, stream=stream)
@@ -207,6 +217,8 @@ class Leg:
     def step_name(self, static_worlds=False):
         if static_worlds:
             return "mv_set_cameras(device) + mv_render_batch (worlds uploaded once)"
+        if self.moves:
+            return "mv_move_voxels(device) + mv_set_cameras(device) + mv_render_batch"
         if self.sparse:
             return "mv_update_voxels(device) + mv_set_cameras(device) + mv_render_batch"
         return "mv_upload_worlds(device) + mv_set_cameras(device) + mv_render_batch"
@@ -215,9 +227,9 @@ class Leg:
         self.batch.close()
 
 
-def side_workload(mv, synth, torch, np, wl, index, steps=40, warmup=15, sparse_edits=False):
+def side_workload(mv, synth, torch, np, wl, index, steps=40, warmup=15, sparse_edits=False, object_moves=False):
     """obs/s, rays/s and render time of another workload under the same step definition (a shorter region)."""
-    leg = Leg(mv, synth, torch, np, wl, index, sparse_edits=sparse_edits)
+    leg = Leg(mv, synth, torch, np, wl, index, sparse_edits=sparse_edits, object_moves=object_moves)
     elapsed, render_ms = leg.timed(steps, warmup)
     spec = wl.spec
     out = {"workload": spec.name, "grid": list(spec.grid), "image": [spec.width, spec.height],
@@ -335,9 +347,10 @@ def main() -> int:
     with_others = args.config == 2 and not args.no_other_workloads and not args.static_worlds and not args.sparse_edits
     others = []
     if with_others:
-        others = [(c, synth.generate(c), False) for c in (1, 3, 4)]
-        others.insert(2, (3, synth.generate(3), True))
-        others += [(s.index, synth.generate_extra(name), False) for name, s in synth.EXTRA_SPECS.items()]
+        others = [(c, synth.generate(c), "upload") for c in (1, 3, 4)]
+        others.insert(2, (3, synth.generate(3), "edits"))
+        others.insert(3, (3, synth.generate(3), "moves"))
+        others += [(s.index, synth.generate_extra(name), "upload") for name, s in synth.EXTRA_SPECS.items()]
     leg = Leg(mv, synth, torch, np, wl, args.config, sparse_edits=args.sparse_edits, tiles_per_block=args.tiles_per_block,
               coarse_level=args.coarse_level)
     n, H, W = spec.num_obs, spec.height, spec.width
@@ -347,8 +360,9 @@ def main() -> int:
 
     # ---- side measurements that keep the GPU busy right up to the headline region
     other_results = []
-    for index, other_wl, sparse in others:
-        other_results.append(side_workload(mv, synth, torch, np, other_wl, index, sparse_edits=sparse))
+    for index, other_wl, how in others:
+        other_results.append(side_workload(mv, synth, torch, np, other_wl, index, sparse_edits=how == "edits",
+                                           object_moves=how == "moves"))
         del other_wl
     others = []
     copy_rate = device_copy_rate(torch)

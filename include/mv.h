@@ -128,6 +128,20 @@ int mv_upload_worlds(mv_batch* batch, int32_t first_env, int32_t count, const ui
 int mv_update_voxels(mv_batch* batch, int32_t count, const int32_t* env, const int32_t* voxel_index,
                      const uint8_t* material, int32_t src_is_device, void* hip_stream);
 
+/* Re-stamp objects that moved, from their positions (paper Sec. 3.1-3.2: agents push boxes around and move
+ * themselves; an object occupies whole voxels, an agent's body two of them).  Entry e says that one voxel of an
+ * object of environment env[e] was at from_voxel[e] and is now at to_voxel[e] (linear indices; -1 = nowhere: the
+ * object appears or disappears) and has material[e] (1..num_materials; 0 = nothing to draw).  Every `from` voxel
+ * of the call is emptied first, then every `to` voxel is filled, so objects may swap places, follow each other or
+ * stay where they are (from == to) in one call; two objects must not end in the same voxel.  The same as
+ * mv_update_voxels with one clearing and one filling edit per entry, without the caller building those lists.
+ *   env, from_voxel, to_voxel : [count] int32;  material : [count] uint8; host memory if src_is_device == 0
+ *   (validated: MV_ERR_RANGE, MV_ERR_STATE as for mv_update_voxels, nothing is changed), else device memory (not
+ *   validated; out-of-range entries are skipped).
+ * Errors: MV_ERR_ARG, MV_ERR_RANGE, MV_ERR_STATE, MV_ERR_HIP. */
+int mv_move_voxels(mv_batch* batch, int32_t count, const int32_t* env, const int32_t* from_voxel,
+                   const int32_t* to_voxel, const uint8_t* material, int32_t src_is_device, void* hip_stream);
+
 /* Set all N*A cameras (paper Sec. 3.2: cameras are entities of the state S that Render reads).
  *   cams       : [N*A, 5] float32 rows (x, y, z, yaw, pitch), observation order env*A+agent.
  *   self_voxel : [N*A] int32, linear index of the LOWER voxel of the camera's own 1x1x2 body

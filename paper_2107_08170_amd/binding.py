@@ -20,7 +20,7 @@ FACE_INSIDE, FACE_MISS = 6, 255
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
            "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_step", "mv_host_alloc", "mv_host_free",
            "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records",
-           "mv_debug_set_staged_layers", "mv_render_worlds_noalloc")
+           "mv_debug_set_staged_layers", "mv_render_worlds_noalloc", "mv_move_voxels")
 NOALLOC_SCRATCH_BYTES = 8 << 20
 
 
@@ -71,6 +71,7 @@ def load_library():
     lib.mv_create_batch.argtypes = [C.POINTER(MvConfig), C.POINTER(vp)]
     lib.mv_upload_worlds.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp]
     lib.mv_update_voxels.argtypes = [vp, C.c_int32, vp, vp, vp, C.c_int32, vp]
+    lib.mv_move_voxels.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.c_int32, vp]
     lib.mv_set_cameras.argtypes = [vp, vp, vp, C.c_int32, vp]
     lib.mv_render_batch.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.mv_set_active.argtypes = [vp, vp, C.c_int32, vp]
@@ -210,6 +211,16 @@ class Batch:
             raise ValueError("env, voxel_index and material must live in the same memory space")
         _check(load_library().mv_update_voxels(self._h, count, _as_ptr(env), _as_ptr(voxel_index), _as_ptr(material),
                                                1 if dev else 0, stream))
+
+    def move_voxels(self, env, from_voxel, to_voxel, material, stream: int = 0) -> None:
+        """Objects that moved: ``env``, ``from_voxel``, ``to_voxel`` i32[count] and ``material`` u8[count], all four torch
+        CUDA tensors or all four host arrays."""
+        count = int(env.shape[0])
+        dev = _is_device(env)
+        if any(_is_device(a) != dev for a in (from_voxel, to_voxel, material)):
+            raise ValueError("env, from_voxel, to_voxel and material must live in the same memory space")
+        _check(load_library().mv_move_voxels(self._h, count, _as_ptr(env), _as_ptr(from_voxel), _as_ptr(to_voxel),
+                                             _as_ptr(material), 1 if dev else 0, stream))
 
     def set_cameras(self, cams, self_voxel=None, stream: int = 0) -> None:
         dev = _is_device(cams)

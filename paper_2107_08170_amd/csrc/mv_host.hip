@@ -75,7 +75,7 @@ struct mv_batch {
     uint8_t* d_active = nullptr;      // [N] render mask
     bool all_active = true;
     float* d_fraction = nullptr;      // [N*A] staging for host-supplied bar fractions
-    uint8_t* d_edits = nullptr;       // staging for host-supplied voxel edits (grown on demand)
+    uint8_t* d_edits = nullptr;       // staging for host-supplied voxel edits and moves, 13 bytes per entry (grown on demand)
     size_t edits_capacity = 0;        // in edits
     float* d_cams = nullptr;          // staging for host-supplied cameras
     int32_t* d_self = nullptr;
@@ -389,7 +389,7 @@ int mv_update_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32
             size_t cap = b->edits_capacity ? b->edits_capacity : 4096;
             while (cap < (size_t)count) cap *= 2;
             uint8_t* fresh = nullptr;
-            MV_HIP(hipMalloc((void**)&fresh, cap * 9));
+            MV_HIP(hipMalloc((void**)&fresh, cap * 13));
             MV_HIP(hipStreamSynchronize(stream));
             (void)hipFree(b->d_edits);
             b->d_edits = fresh;
@@ -407,6 +407,59 @@ int mv_update_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32
     MV_HIP(mv::launch_update_voxels(d_env, d_idx, d_mat, count, b->d_vox, b->d_bits, b->d_ztop, b->cfg.num_envs,
                                     b->voxels_per_env, b->cfg.num_materials, b->layout,
                                     mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
+    return MV_OK;
+}
+
+int mv_move_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32_t* from_voxel, const int32_t* to_voxel,
+                   const uint8_t* material, int32_t src_is_device, void* hip_stream)
+{
+    if (!b) return fail(MV_ERR_ARG, "mv_move_voxels: null batch");
+    if (count < 0) return fail(MV_ERR_ARG, "mv_move_voxels: negative count");
+    if (count == 0) return MV_OK;
+    if (!env || !from_voxel || !to_voxel || !material) return fail(MV_ERR_ARG, "mv_move_voxels: null argument");
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_move_voxels: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int32_t* d_env = env;
+    const int32_t* d_from = from_voxel;
+    const int32_t* d_to = to_voxel;
+    const uint8_t* d_mat = material;
+    if (!src_is_device) {
+        for (int32_t e = 0; e < count; ++e) {
+            if (env[e] < 0 || env[e] >= b->cfg.num_envs)
+                return fail(MV_ERR_RANGE, "mv_move_voxels: move %d names environment %d", e, env[e]);
+            if (from_voxel[e] < -1 || from_voxel[e] >= b->voxels_per_env || to_voxel[e] < -1 || to_voxel[e] >= b->voxels_per_env)
+                return fail(MV_ERR_RANGE, "mv_move_voxels: move %d names voxels %d -> %d", e, from_voxel[e], to_voxel[e]);
+            if (material[e] > b->cfg.num_materials)
+                return fail(MV_ERR_RANGE, "mv_move_voxels: move %d has material id %d > %d", e, (int)material[e],
+                            b->cfg.num_materials);
+            if (!b->env_has_grid[env[e]])
+                return fail(MV_ERR_STATE, "mv_move_voxels: environment %d has no grid yet", env[e]);
+        }
+        if ((size_t)count > b->edits_capacity) {
+            size_t cap = b->edits_capacity ? b->edits_capacity : 4096;
+            while (cap < (size_t)count) cap *= 2;
+            uint8_t* fresh = nullptr;
+            MV_HIP(hipMalloc((void**)&fresh, cap * 13));
+            MV_HIP(hipStreamSynchronize(stream));
+            (void)hipFree(b->d_edits);
+            b->d_edits = fresh;
+            b->edits_capacity = cap;
+        }
+        int32_t* s_env = reinterpret_cast<int32_t*>(b->d_edits);
+        int32_t* s_from = s_env + b->edits_capacity;
+        int32_t* s_to = s_from + b->edits_capacity;
+        uint8_t* s_mat = reinterpret_cast<uint8_t*>(s_to + b->edits_capacity);
+        MV_HIP(hipMemcpyAsync(s_env, env, (size_t)count * 4, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipMemcpyAsync(s_from, from_voxel, (size_t)count * 4, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipMemcpyAsync(s_to, to_voxel, (size_t)count * 4, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipMemcpyAsync(s_mat, material, (size_t)count, hipMemcpyHostToDevice, stream));
+        MV_HIP(hipStreamSynchronize(stream));
+        d_env = s_env; d_from = s_from; d_to = s_to; d_mat = s_mat;
+    }
+    MV_HIP(mv::launch_move_voxels(d_env, d_from, d_to, d_mat, count, b->d_vox, b->d_bits, b->d_ztop, b->cfg.num_envs,
+                                  b->voxels_per_env, b->cfg.num_materials, b->layout,
+                                  mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
     return MV_OK;
 }
 

@@ -101,6 +101,10 @@ hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, 
                                 uint8_t* vox, uint64_t* bits, int32_t* ztop, int num_envs, int voxels_per_env,
                                 int num_materials, const GridLayout& g, const HeightFeedback& heights,
                                 hipStream_t stream);
+hipError_t launch_move_voxels(const int32_t* env, const int32_t* from_voxel, const int32_t* to_voxel,
+                              const uint8_t* material, int count, uint8_t* vox, uint64_t* bits, int32_t* ztop,
+                              int num_envs, int voxels_per_env, int num_materials, const GridLayout& g,
+                              const HeightFeedback& heights, hipStream_t stream);
 hipError_t launch_cameras(const float* cams, const int32_t* self_voxel, CameraRecord* rec, int num_obs,
                           double tan_half_x, double tan_half_y, int plane_voxels, hipStream_t stream);
 struct BarParams {

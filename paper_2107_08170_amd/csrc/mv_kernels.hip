@@ -414,7 +414,7 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= count) return;
     const int n = env[e], idx = voxel_index[e];
-    const int m = material[e];
+    const int m = material ? material[e] : 0;           // no material array: every entry empties its voxel
     if ((m != 0) != kFill) return;
     if (n < 0 || n >= num_envs || idx < 0 || idx >= voxels_per_env || m > num_materials) return;
     const int XY = g.X * g.Y;
@@ -441,6 +441,21 @@ hipError_t launch_update_voxels(const int32_t* env, const int32_t* voxel_index, 
     hipLaunchKernelGGL(update_voxels_kernel<false>, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
                        material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g, heights);
     hipLaunchKernelGGL(update_voxels_kernel<true>, dim3((count + 255) / 256), dim3(256), 0, stream, env, voxel_index,
+                       material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g, heights);
+    return hipGetLastError();
+}
+
+// Objects that moved: every voxel an object left is emptied (first launch, no material array), then every voxel an
+// object is in now is filled with the object's material (second launch); negative indices are skipped by the kernel.
+hipError_t launch_move_voxels(const int32_t* env, const int32_t* from_voxel, const int32_t* to_voxel,
+                              const uint8_t* material, int count, uint8_t* vox, uint64_t* bits, int32_t* ztop,
+                              int num_envs, int voxels_per_env, int num_materials, const GridLayout& g,
+                              const HeightFeedback& heights, hipStream_t stream)
+{
+    hipLaunchKernelGGL(update_voxels_kernel<false>, dim3((count + 255) / 256), dim3(256), 0, stream, env, from_voxel,
+                       static_cast<const uint8_t*>(nullptr), count, vox, bits, ztop, num_envs, voxels_per_env, num_materials,
+                       g, heights);
+    hipLaunchKernelGGL(update_voxels_kernel<true>, dim3((count + 255) / 256), dim3(256), 0, stream, env, to_voxel,
                        material, count, vox, bits, ztop, num_envs, voxels_per_env, num_materials, g, heights);
     return hipGetLastError();
 }

@@ -272,6 +272,34 @@ def dynamic_step(wl: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     return cur, cams, selfv
 
 
+def dynamic_positions(wl: Workload) -> Tuple[np.ndarray, np.ndarray]:
+    """Copies of the current floor cells (j*X+i) of the boxes i32[N,32] and of the agents i32[N,A]."""
+    return wl._dyn["box"].copy(), wl._dyn["agent"].copy()
+
+
+def object_moves(wl: Workload, before: Tuple[np.ndarray, np.ndarray],
+                 after: Tuple[np.ndarray, np.ndarray]) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """The step from ``before`` to ``after`` (two results of dynamic_positions) as one entry per object voxel:
+    (env i32[n], from_voxel i32[n], to_voxel i32[n], material u8[n]); boxes are one voxel at k=1, agent bodies two
+    (k=1 and k=2).  Objects that stayed where they were are listed too (from == to)."""
+    X, Y, _ = wl.spec.grid
+    d = wl._dyn
+    N = before[0].shape[0]
+    plane = X * Y
+    env, frm, to, mat = [], [], [], []
+
+    def add(cells_before, cells_after, layer, materials):
+        n_idx = np.broadcast_to(np.arange(N, dtype=np.int32)[:, None], cells_before.shape)
+        env.append(n_idx.reshape(-1)); frm.append((layer * plane + cells_before).reshape(-1))
+        to.append((layer * plane + cells_after).reshape(-1)); mat.append(materials.reshape(-1))
+
+    add(before[0], after[0], 1, d["box_mat"])
+    add(before[1], after[1], 1, d["body_mat"][:, :, 0])
+    add(before[1], after[1], 2, d["body_mat"][:, :, 1])
+    return (np.concatenate(env).astype(np.int32), np.concatenate(frm).astype(np.int32),
+            np.concatenate(to).astype(np.int32), np.concatenate(mat).astype(np.uint8))
+
+
 def grid_edits(before: np.ndarray, after: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """The voxels that differ between two batches of grids, as (env i32[n], voxel_index i32[n],
     material u8[n]) with the material of ``after``: each changed voxel appears exactly once."""

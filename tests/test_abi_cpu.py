@@ -105,6 +105,7 @@ def test_null_arguments(lib):
     assert lib.mv_set_cameras(None, None, None, 0, None) == binding.MV_ERR_ARG
     assert lib.mv_render_batch(None, None, None, None, None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_fetch_observations(None, None, None, 0, 1, None, None, None) == binding.MV_ERR_ARG
+    assert lib.mv_move_voxels(None, 1, None, None, None, None, 0, None) == binding.MV_ERR_ARG
     assert lib.mv_step(None, None, None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_step(None, C.byref(binding.MvStepInputs()), None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_host_alloc(None, 16) == binding.MV_ERR_ARG

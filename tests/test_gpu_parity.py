@@ -1013,6 +1013,47 @@ def test_step_captured_over_low_worlds_replays_over_taller_ones(lib, orc):
     batch.debug_set_staged_layers(0)
 
 
+def test_objects_moved_from_their_positions(lib, orc):
+    """mv_move_voxels: the dynamic workload's boxes and agent bodies re-stamped from (old cell, new cell, material)
+    lists -- no grid diff on the host.  After every step the batch must render what a batch with the freshly
+    uploaded grid renders, bit for bit, and what the oracle renders from that grid; device and host lists alike.
+    Objects follow each other and swap into vacated cells within one call."""
+    wl = synth.generate(3, num_envs=96)
+    spec = wl.spec
+    moved = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0], wl.self_voxel[0])
+    fresh = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0], wl.self_voxel[0])
+    followed = 0
+    for step in range(5):
+        before = synth.dynamic_positions(wl)
+        vox, cams, selfv = synth.dynamic_step(wl)
+        after = synth.dynamic_positions(wl)
+        env, frm, to, mat = synth.object_moves(wl, before, after)
+        # cells that one object left and another entered in this very step
+        left = set(zip(env[frm != to].tolist(), frm[frm != to].tolist()))
+        followed += len(left & set(zip(env[frm != to].tolist(), to[frm != to].tolist())))
+        if step % 2 == 0:
+            moved.batch.move_voxels(*(torch.from_numpy(a).cuda() for a in (env, frm, to, mat)), stream=_stream())
+        else:
+            moved.batch.move_voxels(env, frm, to, mat, stream=_stream())
+        cams_d, self_d = torch.from_numpy(cams).cuda(), torch.from_numpy(selfv).cuda()
+        moved.batch.set_cameras(cams_d, self_d, stream=_stream())
+        fresh.batch.upload_worlds(torch.from_numpy(vox).cuda(), None, stream=_stream())
+        fresh.batch.set_cameras(cams_d, self_d, stream=_stream())
+        moved.render()
+        fresh.render()
+        a, b = moved.numpy(), fresh.numpy()
+        for name in ("rgb", "depth", "material", "hit_index", "face"):
+            np.testing.assert_array_equal(getattr(a, name).view(np.uint8), getattr(b, name).view(np.uint8),
+                                          err_msg=f"step {step} {name}")
+        ob = _oracle_for(orc, spec, vox, wl.palette, cams, selfv)
+        _compare_all(ob, moved, label=f"moved objects, step {step}", chunk=192)
+    assert followed > 0                      # the case the clears-before-fills order exists for did occur
+    with pytest.raises(binding.MvError) as err:
+        moved.batch.move_voxels(np.array([0], np.int32), np.array([spec.grid[0] * spec.grid[1] * spec.grid[2]], np.int32),
+                                np.array([0], np.int32), np.array([1], np.uint8))
+    assert err.value.code == binding.MV_ERR_RANGE
+
+
 def test_an_object_enters_the_voxel_another_one_leaves_in_the_same_call(lib, orc):
     """One edit list that empties a voxel and fills the same voxel again (object 1 leaves, object 2 enters),
     next to ordinary moves: clears are applied before fills whatever their order in the list, so the voxel ends
