@@ -525,8 +525,7 @@ struct alignas(16) ScanClass {
     float uexit;        // U - Pu: distance to the far side of the grid along u
     float dist_v;       // distance from the camera to the first v plane in this direction (>= 0)
     float nv_max;       // v planes between the camera cell and the grid boundary in this direction
-    float dist_z;       // the same two along z (the grid is cut at the top solid layer)
-    float nz_max;
+    float spare[2];     // (the z counterparts of those two depend on the image row: RowRecord holds them)
     float Pu_err;       // what rounding took from the mirrored coordinate: (U - P) - Pu exactly, 0 if not mirrored
     int   addr0;        // LDS byte address of the camera's row in this class's row array
     int   i0;           // camera cell along u (mirrored)
@@ -1121,6 +1120,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             const bool zneg = (dz + 0.0f) < 0.0f;
             rr.rcp_z = safe_rcp(dz + 0.0f);
             const float dt_z = fabsf(rr.rcp_z);
+            // (a rising ray of a camera above the solids leaves the cut grid at its first z plane: any positive
+            // distance will do, the top of its real cell is one)
             const float dist_z = fabsf((float)(zneg ? kc : k0 + 1) - P[2]);
             const float nz_max = (float)(zneg ? kc : zlim - 1 - kc);
             rr.t0_z = dist_z * dt_z;
@@ -1193,10 +1194,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         // first plane along v: the upper plane of the camera's cell for rising v, the lower one otherwise
         c.dist_v = fabsf((float)(vneg ? j0 : j0 + 1) - pv);
         c.nv_max = (float)(vneg ? j0 : V - 1 - j0);
-        // along z (a rising ray of a camera above the solids leaves the cut grid at its first z plane: any
-        // positive distance will do, the top of its real cell is one)
-        c.dist_z = fabsf((float)(zneg ? kc : k0 + 1) - P[2]);
-        c.nz_max = (float)(zneg ? kc : zlim - 1 - kc);
+        c.spare[0] = c.spare[1] = 0.0f;
         const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? sxw : 0) : 2 * sxw + (neg ? syw : 0));
         c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(kc * V + j0));
         c.sv = vneg ? -8 : 8;
