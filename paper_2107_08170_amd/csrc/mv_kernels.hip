@@ -525,7 +525,8 @@ struct alignas(16) ScanClass {
     float uexit;        // U - Pu: distance to the far side of the grid along u
     float dist_v;       // distance from the camera to the first v plane in this direction (>= 0)
     float nv_max;       // v planes between the camera cell and the grid boundary in this direction
-    float spare[2];     // (the z counterparts of those two depend on the image row: RowRecord holds them)
+    float zero[2];      // 0, 0: where a ray's two crossing counters start (the z counterparts of the two values
+                        // above depend on the image row: RowRecord holds them)
     float Pu_err;       // what rounding took from the mirrored coordinate: (U - P) - Pu exactly, 0 if not mirrored
     int   addr0;        // LDS byte address of the camera's row in this class's row array
     int   i0;           // camera cell along u (mirrored)
@@ -764,7 +765,8 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 
     // crossings made so far along v and z (without sign; the directions sit in the class), and the parameters
     // of the next ones: t_v = n_v*dt_v + t0_v, t_z likewise
-    float t_v, t_z, n_v = 0.0f, n_z = 0.0f;
+    // (the counters start from the two zero words of the record: registers the load has filled anyway)
+    float t_v, t_z, n_v = c.zero[0], n_z = c.zero[1];
     uint32_t addr = (uint32_t)c.addr0;
     uint64_t r, in_range;
     int i_last;
@@ -853,29 +855,30 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
         }
     } else
     // The loop in assembly: the compiler's structured control flow spends about ten scalar instructions per turn
-    // on lane masks (two breaks per trip); written out, a turn needs two.  Lanes that are done simply leave
+    // on lane masks (two breaks per trip); written out, a turn needs one, the branch: the two comparisons that
+    // decide whether a lane goes on write the execution mask themselves.  Lanes that are done simply leave
     // the execution mask (it only ever shrinks; restored after the loop), so every register of a finished lane
     // keeps the values of its last turn.  The cell index alternates between i_a and i_b from turn to turn; a
     // turn that writes i_a copies it to i_b, so that i_b holds the last cell of a lane whichever turn it left in.
     // The first turn is peeled: it reads the first crossings straight from t0_v / t0_z and starts the crossing
-    // counters instead of incrementing them.  The v-or-z decision of a turn is taken at its top (VCC), well ahead
-    // of the selects that read it (a vector instruction may not read a lane mask within two instructions of the
-    // one that wrote it).
+    // counters instead of incrementing them; the loop proper holds four turns per backward branch.  The v-or-z
+    // decision of a turn is taken at its top (VCC), well ahead of the selects that read it (a vector instruction may
+    // not read a lane mask within two instructions of the one that wrote it).  Every kind of instruction costs this
+    // kernel about the same issue time, so what counts is how many there are (measured: the mask-writing
+    // comparisons and the longer unrolling together -1.3 %).
     {
         uint64_t exec_save, m_go, m_empty;
         float t_out, tmp;
         int sh;
         // the run of cells [IFROM, ITO] of the current row: ITO from the parameter at which the ray leaves the row
         // (TOUT, NARROW: capped at the grid exit; else the cell is clamped to U - 1), then the two shifts
-#define MV_ASM_TEST(TV, TZ, IFROM, ITO, TOUT_AND_CELL)                                  \
+#define MV_ASM_TEST(TV, TZ, IFROM, ITO, TOUT_AND_CELL, WAIT)                            \
             "v_cmp_le_f32_e32 vcc, " TV ", " TZ "\n\t"                                   \
             TOUT_AND_CELL(TV, TZ, ITO)                                                   \
-            "v_cmp_lt_f32_e64 %[mgo], %[tout], %[tend]\n\t"                             \
-            "s_waitcnt lgkmcnt(0)\n\t"                                                  \
+            WAIT                                                                        \
             "v_lshrrev_b64 %[r], " IFROM ", %[row]\n\t"                                 \
             "v_xad_u32 %[sh], " ITO ", -1, " IFROM "\n\t"                               \
-            "v_lshlrev_b64 %[inr], %[sh], %[r]\n\t"                                     \
-            "v_cmp_eq_u64_e64 %[mempty], 0, %[inr]\n\t"
+            "v_lshlrev_b64 %[inr], %[sh], %[r]\n\t"
 #define MV_ASM_CELL_NARROW(TV, TZ, ITO)                                                 \
             "v_min3_f32 %[tout], " TV ", " TZ ", %[tend]\n\t"                            \
             "v_fma_f32 %[tmp], %[tout], |%[du]|, %[pu]\n\t"                             \
@@ -885,8 +888,11 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
             "v_fma_f32 %[tmp], %[tout], |%[du]|, %[pu]\n\t"                             \
             "v_cvt_i32_f32_e32 %[tmp], %[tmp]\n\t"                                      \
             "v_min_i32_e32 " ITO ", %[tmp], %[um1]\n\t"
+        // lanes that found a solid cell leave first (their in_range stays non-zero), then the lanes whose ray leaves
+        // the grid in this row (theirs is zero): each comparison writes the execution mask itself
 #define MV_ASM_LEAVE                                                                    \
-            "s_and_b64 exec, %[mgo], %[mempty]\n\t"                                     \
+            "v_cmpx_eq_u64_e64 %[mempty], 0, %[inr]\n\t"                                \
+            "v_cmpx_lt_f32_e64 %[mgo], %[tout], %[tend]\n\t"                            \
             "s_cbranch_execz 2f\n\t"
 #define MV_ASM_NEXT_ROW                                                                 \
             "v_cndmask_b32_e32 %[tmp], %[sz], %[sv], vcc\n\t"                           \
@@ -906,19 +912,27 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
             "v_add_f32_e32 %[nz], %[nz], %[tmp]\n\t"                                    \
             "v_fma_f32 %[tv], %[nv], |%[rv]|, %[t0v]\n\t"                               \
             "v_fma_f32 %[tz], %[nz], |%[rz]|, %[t0z]\n\t"
+#define MV_ASM_WAIT "s_waitcnt lgkmcnt(0)\n\t"
+#define MV_ASM_TURN_TO_A(CELL)                                                          \
+            MV_ASM_TEST("%[tv]", "%[tz]", "%[ib]", "%[ia]", CELL, MV_ASM_WAIT)           \
+            "v_mov_b32_e32 %[ib], %[ia]\n\t"                                            \
+            MV_ASM_LEAVE                                                                \
+            MV_ASM_ADVANCE
+#define MV_ASM_TURN_TO_B(CELL)                                                          \
+            MV_ASM_TEST("%[tv]", "%[tz]", "%[ia]", "%[ib]", CELL, MV_ASM_WAIT)           \
+            MV_ASM_LEAVE                                                                \
+            MV_ASM_ADVANCE
+        // (the first row has arrived when the statement starts: it is one of its inputs)
 #define MV_ASM_LOOP(CELL)                                                               \
             "s_mov_b64 %[save], exec\n\t"                                               \
-            MV_ASM_TEST("%[t0v]", "%[t0z]", "%[ia]", "%[ib]", CELL)                      \
+            MV_ASM_TEST("%[t0v]", "%[t0z]", "%[ia]", "%[ib]", CELL, "")                  \
             MV_ASM_LEAVE                                                                \
             MV_ASM_FIRST_ADVANCE                                                        \
             "1:\n\t"                                                                    \
-            MV_ASM_TEST("%[tv]", "%[tz]", "%[ib]", "%[ia]", CELL)                        \
-            "v_mov_b32_e32 %[ib], %[ia]\n\t"                                            \
-            MV_ASM_LEAVE                                                                \
-            MV_ASM_ADVANCE                                                              \
-            MV_ASM_TEST("%[tv]", "%[tz]", "%[ia]", "%[ib]", CELL)                        \
-            MV_ASM_LEAVE                                                                \
-            MV_ASM_ADVANCE                                                              \
+            MV_ASM_TURN_TO_A(CELL)                                                      \
+            MV_ASM_TURN_TO_B(CELL)                                                      \
+            MV_ASM_TURN_TO_A(CELL)                                                      \
+            MV_ASM_TURN_TO_B(CELL)                                                      \
             "s_branch 1b\n"                                                             \
             "2:\n\t"                                                                    \
             "s_mov_b64 exec, %[save]\n\t"
@@ -929,7 +943,7 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
                   [nv] "+v"(n_v), [nz] "+v"(n_z)                                                                      \
                 : [tend] "v"(t_end), [du] "v"(du), [pu] "v"(c.Pu), [sv] "v"(c.sv), [sz] "v"(c.sz), [rv] "v"(rcp_v),  \
                   [rz] "v"(rcp_z), [t0v] "v"(t0_v), [t0z] "v"(t0_z), [um1] "v"(c.um1)                                 \
-                : "vcc", "memory"
+                : "vcc", "scc", "memory"
         if (kNarrow) asm volatile(MV_ASM_LOOP(MV_ASM_CELL_NARROW) MV_ASM_OPERANDS);
         else         asm volatile(MV_ASM_LOOP(MV_ASM_CELL_WIDE) MV_ASM_OPERANDS);
 #undef MV_ASM_OPERANDS
@@ -937,6 +951,9 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 #undef MV_ASM_ADVANCE
 #undef MV_ASM_FIRST_ADVANCE
 #undef MV_ASM_NEXT_ROW
+#undef MV_ASM_WAIT
+#undef MV_ASM_TURN_TO_A
+#undef MV_ASM_TURN_TO_B
 #undef MV_ASM_LEAVE
 #undef MV_ASM_CELL_WIDE
 #undef MV_ASM_CELL_NARROW
@@ -1194,7 +1211,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         // first plane along v: the upper plane of the camera's cell for rising v, the lower one otherwise
         c.dist_v = fabsf((float)(vneg ? j0 : j0 + 1) - pv);
         c.nv_max = (float)(vneg ? j0 : V - 1 - j0);
-        c.spare[0] = c.spare[1] = 0.0f;
+        c.zero[0] = c.zero[1] = 0.0f;
         const uint32_t array_off = off_rows + 8u * (uint32_t)(xmaj ? (neg ? sxw : 0) : 2 * sxw + (neg ? syw : 0));
         c.addr0 = (int)(lds_base + array_off + 8u * (uint32_t)(kc * V + j0));
         c.sv = vneg ? -8 : 8;
