@@ -190,6 +190,48 @@ int mvo_draw_bars(const mvo_batch* b, int32_t first_obs, int32_t count, uint8_t*
     return 0;
 }
 
+int mvo_draw_overlay(const mvo_batch* b, int32_t first_obs, int32_t count, uint8_t* rgb, const mvo_rect* rects,
+                     int32_t num_rects, const float* values, int32_t values_per_obs, const uint8_t* active)
+{
+    if (!b || !rgb || !rects || num_rects <= 0 || values_per_obs < 0) return -1;
+    const int32_t W = b->cfg.width, H = b->cfg.height;
+    if (first_obs < 0 || count <= 0 || first_obs > b->cfg.num_envs * b->cfg.agents_per_env - count) return -3;
+    for (int32_t k = 0; k < num_rects; ++k) {
+        const mvo_rect* q = &rects[k];
+        if (q->width <= 0 || q->height <= 0 || q->x < 0 || q->y < 0 || q->x > W - q->width || q->y > H - q->height)
+            return -1;
+        if (q->kind > 2) return -1;
+        if (q->kind != 0 && (!values || q->value_index >= values_per_obs)) return -1;
+    }
+    for (int32_t o = 0; o < count; ++o) {
+        if (active && !active[(first_obs + o) / b->cfg.agents_per_env]) continue;
+        uint8_t* img = rgb + (size_t)o * H * W * 3;
+        for (int32_t k = 0; k < num_rects; ++k) {           /* in list order: later primitives paint over earlier ones */
+            const mvo_rect* q = &rects[k];
+            int32_t filled = 0;
+            if (q->kind != 0) {
+                const int32_t extent = q->kind == 1 ? q->width : q->height;
+                volatile float prod = values[(size_t)o * values_per_obs + q->value_index] * (float)extent;
+                volatile float sum = prod + 0.5f;
+                float n = floorf(sum);
+                if (!(n > 0.0f)) n = 0.0f;
+                if (n > (float)extent) n = (float)extent;
+                filled = (int32_t)n;
+            }
+            for (int32_t r = 0; r < q->height; ++r)
+                for (int32_t c = 0; c < q->width; ++c) {
+                    int in_front = 1;                                       /* kind 0: the whole rectangle */
+                    if (q->kind == 1) in_front = c < filled;                /* columns from the left edge */
+                    if (q->kind == 2) in_front = q->height - 1 - r < filled; /* rows from the bottom edge */
+                    const uint8_t* col = in_front ? q->rgb : q->rest_rgb;
+                    uint8_t* px = img + ((size_t)(q->y + r) * W + (size_t)(q->x + c)) * 3;
+                    px[0] = col[0]; px[1] = col[1]; px[2] = col[2];
+                }
+        }
+    }
+    return 0;
+}
+
 int mvo_camera_record(const mvo_batch* b, int32_t obs, float rec[12])
 {
     if (!b || !rec || !b->cams_ready) return -1;

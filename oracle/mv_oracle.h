@@ -83,6 +83,23 @@ int  mvo_draw_bars(const mvo_batch* b, int32_t first_obs, int32_t count, uint8_t
                    int32_t x, int32_t y, int32_t width, int32_t height, const uint8_t fill_rgb[3],
                    const uint8_t empty_rgb[3], const uint8_t* active);
 
+/* Overlay of geometric primitives (paper App. A.2: a pixel-space GUI of geometric primitives drawn over the
+ * observation).  A primitive is an axis-aligned rectangle of pixels that lies inside the image.  Kind 0 paints it
+ * in one colour.  Kinds 1 and 2 are gauges: with v = values[o * values_per_obs + value_index] and n =
+ * floor(v * extent + 0.5) clamped to 0..extent (float32 product and sum, as for the bar), kind 1 paints the n
+ * leftmost columns (extent = width) and kind 2 the n lowest rows (extent = height) in `rgb`, the rest of the
+ * rectangle in `rest_rgb`.  The primitives are painted in list order: a later one covers an earlier one.
+ * `rgb` holds `count` observations starting with observation first_obs.  Returns 0, -1 (argument) or -3 (range). */
+typedef struct {
+    int32_t x, y, width, height;
+    uint8_t rgb[3];
+    uint8_t kind;
+    uint8_t rest_rgb[3];
+    uint8_t value_index;
+} mvo_rect;
+int  mvo_draw_overlay(const mvo_batch* b, int32_t first_obs, int32_t count, uint8_t* rgb, const mvo_rect* rects,
+                      int32_t num_rects, const float* values, int32_t values_per_obs, const uint8_t* active);
+
 /* The 12-float camera record (P, F, R, U) of one observation and the float32 ray direction of
  * one pixel, exactly as the renderer uses them. */
 int  mvo_camera_record(const mvo_batch* b, int32_t obs, float rec[12]);

@@ -91,6 +91,7 @@ def _bind(lib):
     lib.mvo_render.argtypes = [vp, C.c_int32, C.c_int32] + [vp] * 8 + [C.c_int32]
     lib.mvo_render_pixels.argtypes = [vp, C.c_int64] + [vp] * 11
     lib.mvo_draw_bars.argtypes = [vp, C.c_int32, C.c_int32, vp, vp] + [C.c_int32] * 4 + [vp, vp, vp]
+    lib.mvo_draw_overlay.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, C.c_int32, vp, C.c_int32, vp]
     lib.mvo_camera_record.argtypes = [vp, C.c_int32, vp]
     lib.mvo_pixel_ray.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp]
     lib.mvo_face_intensity.argtypes = [vp, vp]
@@ -99,6 +100,12 @@ def _bind(lib):
     lib.mvd_first_hit_batch.argtypes = [C.c_int32] * 3 + [vp, C.c_int64] + [vp] * 6
     lib.mvd_first_hit_batch.restype = None
     return lib
+
+
+# layout of mvo_rect (24 bytes, no padding)
+RECT_DTYPE = np.dtype([("x", np.int32), ("y", np.int32), ("width", np.int32), ("height", np.int32),
+                       ("rgb", np.uint8, 3), ("kind", np.uint8), ("rest_rgb", np.uint8, 3), ("value_index", np.uint8)])
+assert RECT_DTYPE.itemsize == 24
 
 
 def _ptr(a: Optional[np.ndarray]):
@@ -237,6 +244,27 @@ class OracleBatch:
                                    _ptr(fill), _ptr(empty), _ptr(active))
         if rc != 0:
             raise ValueError(f"mvo_draw_bars failed ({rc})")
+
+    def draw_overlay(self, rgb: np.ndarray, rects, values: Optional[np.ndarray] = None, first_obs: int = 0,
+                     active: Optional[np.ndarray] = None):
+        """Paint a list of primitives into ``rgb`` (u8[count,H,W,3], modified in place).  ``rects`` is a sequence of
+        (x, y, width, height, rgb, kind, rest_rgb, value_index); ``values`` is f32[count, values_per_obs]."""
+        assert rgb.dtype == np.uint8 and rgb.flags.c_contiguous and rgb.shape[1:] == (self.H, self.W, 3)
+        packed = np.zeros(len(rects), RECT_DTYPE)
+        for k, (x, y, w, h, colour, kind, rest, value_index) in enumerate(rects):
+            packed[k] = (x, y, w, h, tuple(colour), kind, tuple(rest), value_index)
+        per_obs = 0
+        if values is not None:
+            values = np.ascontiguousarray(values, dtype=np.float32)
+            assert values.ndim == 2 and values.shape[0] == rgb.shape[0]
+            per_obs = values.shape[1]
+        if active is not None:
+            active = np.ascontiguousarray(active, dtype=np.uint8)
+            assert active.shape == (self.N,)
+        rc = _load().mvo_draw_overlay(self._h, first_obs, rgb.shape[0], _ptr(rgb), _ptr(packed), len(rects),
+                                      _ptr(values), per_obs, _ptr(active))
+        if rc != 0:
+            raise ValueError(f"mvo_draw_overlay failed ({rc})")
 
     def camera_record(self, obs: int) -> np.ndarray:
         rec = np.empty(12, np.float32)

@@ -511,6 +511,60 @@ def test_indicator_bar_closed_form(orc):
         b.draw_bars(rgb, fractions, 60, 3, 20, 4, (0, 0, 0), (0, 0, 0))      # sticks out of the image
 
 
+def test_overlay_rectangles_paint_in_list_order(orc):
+    """Solid primitives against NumPy slice assignment in the same order: later rectangles cover earlier ones,
+    nothing outside any rectangle changes, inactive environments are skipped, bad lists are refused."""
+    b = orc.OracleBatch(2, 2, (4, 4, 4), 64, 40, 2)
+    rects = [(2, 3, 30, 20, (200, 1, 2), 0, (0, 0, 0), 0),
+             (10, 10, 40, 12, (3, 210, 4), 0, (0, 0, 0), 0),       # overlaps the first
+             (25, 0, 6, 40, (5, 6, 220), 0, (0, 0, 0), 0),         # a full-height stripe over both
+             (63, 39, 1, 1, (7, 8, 9), 0, (0, 0, 0), 0)]           # the last pixel of the image
+    rgb = np.full((4, 40, 64, 3), 77, np.uint8)
+    b.draw_overlay(rgb, rects, active=np.array([1, 0], np.uint8))
+    want = np.full((40, 64, 3), 77, np.uint8)
+    for x, y, w, h, colour, *_ in rects:
+        want[y:y + h, x:x + w] = colour
+    assert (want[11, 26] == (5, 6, 220)).all() and (want[11, 12] == (3, 210, 4)).all() and (want[4, 4] == (200, 1, 2)).all()
+    np.testing.assert_array_equal(rgb[0], want)
+    np.testing.assert_array_equal(rgb[1], want)
+    assert (rgb[2:] == 77).all()                      # environment 1 is inactive
+    for bad in ([(60, 3, 20, 4, (0, 0, 0), 0, (0, 0, 0), 0)],       # sticks out of the image
+                [(0, 0, 4, 4, (0, 0, 0), 3, (0, 0, 0), 0)],        # no such kind
+                [(0, 0, 4, 4, (0, 0, 0), 1, (0, 0, 0), 0)]):       # a gauge without values
+        with pytest.raises(ValueError):
+            b.draw_overlay(rgb, bad)
+    with pytest.raises(ValueError):                                # a gauge whose value column does not exist
+        b.draw_overlay(rgb, [(0, 0, 4, 4, (0, 0, 0), 1, (0, 0, 0), 2)], values=np.zeros((4, 2), np.float32))
+
+
+def test_overlay_gauges_closed_form(orc):
+    """A gauge shows round-half-up(value * extent) columns from the left (kind 1) or rows from the bottom (kind 2),
+    clamped to the rectangle, with exact rationals as the reference; a rightward gauge is the indicator bar."""
+    b = orc.OracleBatch(3, 2, (4, 4, 4), 64, 40, 2)
+    values = np.array([[0.0, 1.0], [1.0, 0.0], [0.5, 0.28], [0.28, 0.5], [0.999, -3.0], [1.7, 0.126]], np.float32)
+    front, rest = (250, 10, 20), (1, 2, 3)
+    x, y, w, h = 5, 3, 20, 25
+    rects = [(x, y, w, h, front, 2, rest, 1),                      # upward gauge on column 1 of the values
+             (40, 30, 20, 4, front, 1, rest, 0)]                   # rightward gauge on column 0
+    rgb = np.full((6, 40, 64, 3), 9, np.uint8)
+    b.draw_overlay(rgb, rects, values=values)
+    bars = np.full((6, 40, 64, 3), 9, np.uint8)
+    b.draw_bars(bars, values[:, 0].copy(), 40, 30, 20, 4, front, rest)
+    seen = set()
+    for o in range(6):
+        rows = min(h, max(0, int(Fraction(float(values[o, 1])) * h + Fraction(1, 2))))
+        seen.add(rows)
+        up = rgb[o, y:y + h, x:x + w]
+        assert (up[h - rows:] == np.array(front, np.uint8)).all()          # the lowest rows
+        assert (up[:h - rows] == np.array(rest, np.uint8)).all()
+        np.testing.assert_array_equal(rgb[o, 30:34, 40:60], bars[o, 30:34, 40:60])
+        outside = rgb[o].copy()
+        outside[y:y + h, x:x + w] = 9
+        outside[30:34, 40:60] = 9
+        assert (outside == 9).all()
+    assert seen == {25, 0, 7, 13, 3}                  # 0.28 * 25 = 7 exactly, 0.5 * 25 = 12.5 rounds up, 0.126 * 25 = 3.15
+
+
 def test_pitched_camera_floor_landing_points(orc):
     """Closed form for a pitched, yawed camera over a solid floor: the pixel ray
     d = F + sx*R + sy*U with F = (cp*cy, cp*sy, sp), R = tx*(sy_, -cy_, 0), U = ty*(-sp*cy, -sp*sy, cp)

@@ -54,6 +54,11 @@ MISTAKES = [
      "double ta = ((d[a] > 0.0 ? (double)dim[a] : 0.0) - P[a]) / d[a];"),
     ("sky colour channels reversed", "mv_oracle.c", "out->rgb[0] = b->cfg.sky_rgb[0];", "out->rgb[0] = b->cfg.sky_rgb[2];"),
     ("bar width truncated", "mv_oracle.c", "volatile float sum = prod + 0.5f;\n        float cols", "volatile float sum = prod;\n        float cols"),
+    ("overlay: primitives painted in reverse order", "mv_oracle.c", "const mvo_rect* q = &rects[k];\n            int32_t filled = 0;", "const mvo_rect* q = &rects[num_rects - 1 - k];\n            int32_t filled = 0;"),
+    ("overlay: upward gauge fills from the top", "mv_oracle.c", "in_front = q->height - 1 - r < filled;", "in_front = r < filled;"),
+    ("overlay: gauge length truncated", "mv_oracle.c", "volatile float sum = prod + 0.5f;\n                float n", "volatile float sum = prod;\n                float n"),
+    ("overlay: upward gauge measured against the width", "mv_oracle.c", "const int32_t extent = q->kind == 1 ? q->width : q->height;", "const int32_t extent = q->width;"),
+    ("overlay: gauge reads the first value column", "mv_oracle.c", "values[(size_t)o * values_per_obs + q->value_index]", "values[(size_t)o * values_per_obs]"),
     ("edits land one voxel further", "mv_oracle.c", "(size_t)voxel_index[e]] = material[e];", "(size_t)voxel_index[e] + 1] = material[e];"),
     ("margin: the crossing's own axis not skipped", "mv_oracle.c", "        if (a == axis) continue;\n        double q = P[a] + t * d[a];",
      "        double q = P[a] + t * d[a];"),
@@ -89,6 +94,8 @@ def _battery(orc):
     yield lambda: pins.test_exact_zero_direction_components(orc)
     yield lambda: pins.test_sparse_edits_equal_a_fresh_upload(orc)
     yield lambda: pins.test_indicator_bar_closed_form(orc)
+    yield lambda: pins.test_overlay_rectangles_paint_in_list_order(orc)
+    yield lambda: pins.test_overlay_gauges_closed_form(orc)
     yield lambda: pins.test_edge_margin_flags_ties_at_the_grid_boundary(orc)
     yield lambda: pins.test_edge_margin_equals_plane_enumeration(orc)
     yield lambda: pins.test_edge_margin_flags_a_grazed_edge_inside_the_grid(orc)
