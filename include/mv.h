@@ -200,6 +200,40 @@ typedef struct {
 int mv_draw_bars(mv_batch* batch, uint8_t* rgb, const float* fraction, const mv_bar* bar,
                  int32_t src_is_device, void* hip_stream);
 
+/* An overlay of geometric primitives drawn over every observation (paper App. A.2: the pixel-space GUI is made of
+ * geometric primitives).  A primitive is an axis-aligned rectangle of pixels that must lie inside the image. */
+#define MV_MAX_OVERLAY_RECTS  32
+#define MV_MAX_OVERLAY_VALUES 8
+enum {
+    MV_RECT_SOLID       = 0,    /* the whole rectangle in `rgb`                                            */
+    MV_RECT_GAUGE_RIGHT = 1,    /* the n leftmost columns in `rgb`, the others in `rest_rgb`               */
+    MV_RECT_GAUGE_UP    = 2     /* the n lowest rows in `rgb`, the others in `rest_rgb`                     */
+};
+typedef struct {
+    int32_t x, y;              /* top-left pixel                                                          */
+    int32_t width, height;     /* in pixels                                                               */
+    uint8_t rgb[3];            /* colour of the rectangle, or of the filled part of a gauge               */
+    uint8_t kind;              /* MV_RECT_*                                                               */
+    uint8_t rest_rgb[3];       /* gauges: colour of the unfilled part                                     */
+    uint8_t value_index;       /* gauges: which of the observation's values sets the filled length        */
+} mv_rect;
+
+/* Paint the primitives into an already rendered colour tensor, in place, after the render on `stream`, in list
+ * order: a later primitive covers an earlier one.
+ *   rgb    : device [N*A, H, W, 3] uint8.
+ *   rects  : HOST memory, num_rects (1..MV_MAX_OVERLAY_RECTS) primitives, read before the call returns.
+ *   values : [N*A, values_per_obs] float32 (0..MV_MAX_OVERLAY_VALUES per observation), host memory if
+ *            src_is_device == 0 (validated: non-finite -> MV_ERR_ARG; copied on `stream`, which is waited for),
+ *            else device memory; may be NULL when no primitive is a gauge.
+ * A gauge of extent e (its width or height) shows n = floor(v*e + 0.5) filled columns or rows, clamped to 0..e,
+ * computed in float32 (the indicator bar's rule; mv_draw_bars is one rightward gauge).  Depth is not touched.
+ * Inactive environments (mv_set_active) are skipped.  With device values the call copies nothing to the host,
+ * allocates nothing and waits for nothing, so it can be captured in a HIP graph.
+ * Errors: MV_ERR_ARG (null, a primitive outside the image, unknown kind, value_index >= values_per_obs, too many
+ * primitives or values), MV_ERR_HIP. */
+int mv_draw_overlay(mv_batch* batch, uint8_t* rgb, const mv_rect* rects, int32_t num_rects, const float* values,
+                    int32_t values_per_obs, int32_t src_is_device, void* hip_stream);
+
 /* One simulator step for the whole batch in a single call (paper App. A.1: a vectorised interface, one
  * step for all N x M agents, with environments that reset on their own; Sec. 3.2: the state changes a
  * little per step and the cameras move with the agents).  In stream order the call applies this step's

@@ -18,7 +18,7 @@ MV_OK, MV_ERR_ARG, MV_ERR_STATE, MV_ERR_RANGE, MV_ERR_CAPACITY, MV_ERR_HIP = 0, 
 FACE_INSIDE, FACE_MISS = 6, 255
 
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
-           "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_step", "mv_host_alloc", "mv_host_free",
+           "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_draw_overlay", "mv_step", "mv_host_alloc", "mv_host_free",
            "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records",
            "mv_debug_set_staged_layers", "mv_render_worlds_noalloc", "mv_move_voxels")
 NOALLOC_SCRATCH_BYTES = 8 << 20
@@ -38,6 +38,15 @@ class MvBar(C.Structure):
     """Mirror of ``mv_bar``."""
     _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("width", C.c_int32), ("height", C.c_int32),
                 ("fill_rgb", C.c_uint8 * 3), ("empty_rgb", C.c_uint8 * 3), ("reserved", C.c_uint8 * 2)]
+
+
+class MvRect(C.Structure):
+    """Mirror of ``mv_rect``."""
+    _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("width", C.c_int32), ("height", C.c_int32),
+                ("rgb", C.c_uint8 * 3), ("kind", C.c_uint8), ("rest_rgb", C.c_uint8 * 3), ("value_index", C.c_uint8)]
+
+
+RECT_SOLID, RECT_GAUGE_RIGHT, RECT_GAUGE_UP = 0, 1, 2
 
 
 class MvStepInputs(C.Structure):
@@ -76,6 +85,7 @@ def load_library():
     lib.mv_render_batch.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.mv_set_active.argtypes = [vp, vp, C.c_int32, vp]
     lib.mv_draw_bars.argtypes = [vp, vp, vp, C.POINTER(MvBar), C.c_int32, vp]
+    lib.mv_draw_overlay.argtypes = [vp, vp, C.POINTER(MvRect), C.c_int32, vp, C.c_int32, C.c_int32, vp]
     lib.mv_step.argtypes = [vp, C.POINTER(MvStepInputs), vp, vp, vp]
     lib.mv_host_alloc.argtypes = [C.POINTER(vp), C.c_size_t]
     lib.mv_host_free.argtypes = [vp]
@@ -244,6 +254,19 @@ class Batch:
         bar.empty_rgb[:] = [int(v) for v in empty_rgb]
         _check(load_library().mv_draw_bars(self._h, _as_ptr(rgb), _as_ptr(fraction), C.byref(bar),
                                            1 if _is_device(fraction) else 0, stream))
+
+    def draw_overlay(self, rgb, rects, values=None, stream: int = 0) -> None:
+        """``rects``: a sequence of (x, y, width, height, rgb, kind, rest_rgb, value_index), painted in this order;
+        ``values``: f32[N*A, k] as a torch CUDA tensor or a host array, or None when no primitive is a gauge."""
+        packed = (MvRect * max(len(rects), 1))()
+        for k, (x, y, width, height, colour, kind, rest, value_index) in enumerate(rects):
+            q = packed[k]
+            q.x, q.y, q.width, q.height, q.kind, q.value_index = x, y, width, height, kind, value_index
+            q.rgb[:] = [int(v) for v in colour]
+            q.rest_rgb[:] = [int(v) for v in rest]
+        per_obs = 0 if values is None else int(values.shape[1])
+        _check(load_library().mv_draw_overlay(self._h, _as_ptr(rgb), packed, len(rects), _as_ptr(values), per_obs,
+                                              1 if values is not None and _is_device(values) else 0, stream))
 
     def step(self, cams, rgb, depth, edits=None, self_voxel=None, done=None, bar_fraction=None, bar=None,
              stream: int = 0) -> None:

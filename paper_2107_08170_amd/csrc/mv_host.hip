@@ -75,6 +75,7 @@ struct mv_batch {
     uint8_t* d_active = nullptr;      // [N] render mask
     bool all_active = true;
     float* d_fraction = nullptr;      // [N*A] staging for host-supplied bar fractions
+    float* d_overlay_values = nullptr; // [N*A][MV_MAX_OVERLAY_VALUES] staging for host-supplied gauge values
     uint8_t* d_edits = nullptr;       // staging for host-supplied voxel edits and moves, 13 bytes per entry (grown on demand)
     size_t edits_capacity = 0;        // in edits
     float* d_cams = nullptr;          // staging for host-supplied cameras
@@ -98,6 +99,7 @@ static void free_batch(mv_batch* b)
     (void)hipFree(b->d_vox); (void)hipFree(b->d_bits); (void)hipFree(b->d_ztop); (void)hipFree(b->d_palette); (void)hipFree(b->d_lut);
     (void)hipFree(b->d_sx); (void)hipFree(b->d_sy); (void)hipFree(b->d_cams); (void)hipFree(b->d_self);
     (void)hipFree(b->d_rec); (void)hipFree(b->d_edits); (void)hipFree(b->d_active); (void)hipFree(b->d_fraction);
+    (void)hipFree(b->d_overlay_values);
     (void)hipFree(b->d_height);
     if (b->h_height) (void)hipHostFree(b->h_height);
     delete b;
@@ -294,6 +296,7 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out)
     alloc((void**)&b->d_rec, (size_t)num_obs * sizeof(mv::CameraRecord));
     alloc((void**)&b->d_active, N);
     alloc((void**)&b->d_fraction, (size_t)num_obs * 4);
+    alloc((void**)&b->d_overlay_values, (size_t)num_obs * MV_MAX_OVERLAY_VALUES * 4);
     alloc((void**)&b->d_height, 4);
     if (e == hipSuccess) e = hipMemset(b->d_height, 0, 4);
     if (e == hipSuccess) e = hipHostMalloc((void**)&b->h_height, 4, hipHostMallocMapped);
@@ -587,6 +590,53 @@ int mv_draw_bars(mv_batch* b, uint8_t* rgb, const float* fraction, const mv_bar*
     bp.empty_packed = (uint32_t)bar->empty_rgb[0] | ((uint32_t)bar->empty_rgb[1] << 8) | ((uint32_t)bar->empty_rgb[2] << 16);
     MV_HIP(mv::launch_bars(rgb, d_fraction, b->all_active ? nullptr : b->d_active, b->num_obs, b->cfg.agents_per_env,
                            b->cfg.width, b->cfg.height, bp, stream));
+    return MV_OK;
+}
+
+int mv_draw_overlay(mv_batch* b, uint8_t* rgb, const mv_rect* rects, int32_t num_rects, const float* values,
+                    int32_t values_per_obs, int32_t src_is_device, void* hip_stream)
+{
+    if (!b || !rgb || !rects) return fail(MV_ERR_ARG, "mv_draw_overlay: null argument");
+    if (num_rects < 1 || num_rects > MV_MAX_OVERLAY_RECTS)
+        return fail(MV_ERR_ARG, "mv_draw_overlay: %d primitives (1..%d)", num_rects, MV_MAX_OVERLAY_RECTS);
+    if (values_per_obs < 0 || values_per_obs > MV_MAX_OVERLAY_VALUES)
+        return fail(MV_ERR_ARG, "mv_draw_overlay: %d values per observation (0..%d)", values_per_obs, MV_MAX_OVERLAY_VALUES);
+    if (!values) values_per_obs = 0;
+    mv::OverlayParams op{};
+    op.count = num_rects;
+    auto packed = [](const uint8_t c[3]) { return (uint32_t)c[0] | ((uint32_t)c[1] << 8) | ((uint32_t)c[2] << 16); };
+    for (int k = 0; k < num_rects; ++k) {
+        const mv_rect& q = rects[k];
+        if (q.width <= 0 || q.height <= 0 || q.x < 0 || q.y < 0 || q.x > b->cfg.width - q.width || q.y > b->cfg.height - q.height)
+            return fail(MV_ERR_ARG, "mv_draw_overlay: primitive %d, %dx%d at (%d,%d), does not fit the %dx%d image", k,
+                        q.width, q.height, q.x, q.y, b->cfg.width, b->cfg.height);
+        if (q.kind != MV_RECT_SOLID && q.kind != MV_RECT_GAUGE_RIGHT && q.kind != MV_RECT_GAUGE_UP)
+            return fail(MV_ERR_ARG, "mv_draw_overlay: primitive %d has unknown kind %d", k, (int)q.kind);
+        if (q.kind != MV_RECT_SOLID && q.value_index >= values_per_obs)
+            return fail(MV_ERR_ARG, "mv_draw_overlay: primitive %d reads value %d of %d", k, (int)q.value_index, values_per_obs);
+        mv::OverlayRect& r = op.rect[k];
+        r.x = q.x; r.y = q.y; r.width = q.width; r.height = q.height;
+        r.front_packed = packed(q.rgb); r.rest_packed = packed(q.rest_rgb);
+        r.kind = q.kind; r.value_index = q.value_index;
+    }
+    DeviceScope scope(b->cfg.device);
+    if (!scope.ok()) return fail(MV_ERR_HIP, "mv_draw_overlay: cannot select device %d", b->cfg.device);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const float* d_values = values;
+    if (values && !src_is_device) {
+        const size_t n = (size_t)b->num_obs * (size_t)values_per_obs;
+        for (size_t i = 0; i < n; ++i)
+            if (!std::isfinite(values[i]))
+                return fail(MV_ERR_ARG, "mv_draw_overlay: value %d of observation %d is not finite", (int)(i % values_per_obs),
+                            (int)(i / values_per_obs));
+        if (n > 0) {
+            MV_HIP(hipMemcpyAsync(b->d_overlay_values, values, n * 4, hipMemcpyHostToDevice, stream));
+            MV_HIP(hipStreamSynchronize(stream));
+        }
+        d_values = b->d_overlay_values;
+    }
+    MV_HIP(mv::launch_overlay(rgb, d_values, values_per_obs, b->all_active ? nullptr : b->d_active, b->num_obs,
+                              b->cfg.agents_per_env, b->cfg.width, b->cfg.height, op, stream));
     return MV_OK;
 }
 

@@ -113,6 +113,19 @@ struct BarParams {
 };
 hipError_t launch_bars(uint8_t* rgb, const float* fraction, const uint8_t* active, int num_obs, int A, int W, int H,
                        const BarParams& bar, hipStream_t stream);
+// overlay primitives, passed to the kernel by value (kind: 0 solid, 1 gauge to the right, 2 gauge upwards)
+constexpr int kMaxOverlayRects = 32;
+struct OverlayRect {
+    int32_t x, y, width, height;
+    uint32_t front_packed, rest_packed;   // r | g<<8 | b<<16
+    int32_t kind, value_index;
+};
+struct OverlayParams {
+    int32_t count;
+    OverlayRect rect[kMaxOverlayRects];
+};
+hipError_t launch_overlay(uint8_t* rgb, const float* values, int values_per_obs, const uint8_t* active, int num_obs, int A,
+                          int W, int H, const OverlayParams& overlay, hipStream_t stream);
 // active[i] = (done[i] == 0) for the n environments of a batch
 hipError_t launch_active_from_done(const uint8_t* done, uint8_t* active, int n, hipStream_t stream);
 // raises the dynamic-LDS limit of the render and pack kernels on the current device (cheap after the first call)

@@ -1441,6 +1441,48 @@ hipError_t launch_bars(uint8_t* rgb, const float* fraction, const uint8_t* activ
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// overlay: one workgroup per observation paints the primitives over the rendered colours, one after the
+// other; the barrier between two primitives (it also waits for the workgroup's stores) keeps the list order
+// where they overlap.
+// ------------------------------------------------------------------------------------------
+__global__ void overlay_kernel(uint8_t* __restrict__ rgb, const float* __restrict__ values, int values_per_obs,
+                               const uint8_t* __restrict__ active, int A, int W, int H, OverlayParams overlay)
+{
+    const int obs = blockIdx.x;
+    if (active && active[obs / A] == 0) return;
+    uint8_t* img = rgb + (size_t)obs * H * W * 3;
+    for (int k = 0; k < overlay.count; ++k) {
+        const OverlayRect& q = overlay.rect[k];
+        int filled = 0;
+        if (q.kind != 0) {
+            // filled columns or rows: one float32 multiply, one float32 add, floor, clamp (NaN falls to 0)
+            const int extent = q.kind == 1 ? q.width : q.height;
+            float n = floorf(__fadd_rn(__fmul_rn(values[(size_t)obs * values_per_obs + q.value_index], (float)extent), 0.5f));
+            n = fminf(fmaxf(n, 0.0f), (float)extent);
+            filled = (int)n;
+        }
+        for (int i = threadIdx.x; i < q.width * q.height; i += blockDim.x) {
+            const int r = i / q.width, c = i - r * q.width;
+            const bool front = q.kind == 0 || (q.kind == 1 ? c < filled : q.height - 1 - r < filled);
+            const uint32_t colour = front ? q.front_packed : q.rest_packed;
+            uint8_t* out = img + ((size_t)(q.y + r) * W + (q.x + c)) * 3;
+            out[0] = (uint8_t)colour;
+            out[1] = (uint8_t)(colour >> 8);
+            out[2] = (uint8_t)(colour >> 16);
+        }
+        if (k + 1 < overlay.count) __syncthreads();
+    }
+}
+
+hipError_t launch_overlay(uint8_t* rgb, const float* values, int values_per_obs, const uint8_t* active, int num_obs, int A,
+                          int W, int H, const OverlayParams& overlay, hipStream_t stream)
+{
+    hipLaunchKernelGGL(overlay_kernel, dim3(num_obs), dim3(256), 0, stream, rgb, values, values_per_obs, active, A, W, H,
+                       overlay);
+    return hipGetLastError();
+}
+
 __global__ void active_from_done_kernel(const uint8_t* __restrict__ done, uint8_t* __restrict__ active, int n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;

@@ -55,6 +55,22 @@ def test_config_struct_layout_matches_header(lib):
     assert cfg.device == 0 and cfg.tiles_per_block == 0 and cfg.num_envs == 0
 
 
+@pytest.mark.parametrize("c_name,mirror", [("mv_bar", "MvBar"), ("mv_rect", "MvRect")])
+def test_overlay_struct_layouts_match_header(c_name, mirror):
+    import subprocess, tempfile
+    cls = getattr(binding, mirror)
+    fields = [f[0] for f in cls._fields_]
+    prog = '#include <stdio.h>\n#include <stddef.h>\n#include "mv.h"\nint main(void){printf("%zu", sizeof(' + c_name + '));' + \
+        "".join(f'printf(" %zu", offsetof({c_name}, {f}));' for f in fields) + "return 0;}"
+    with tempfile.TemporaryDirectory() as tmp:
+        src, exe = os.path.join(tmp, "layout.c"), os.path.join(tmp, "layout")
+        open(src, "w").write(prog)
+        subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), src, "-o", exe], check=True)
+        numbers = [int(x) for x in subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()]
+    assert numbers[0] == C.sizeof(cls)
+    assert numbers[1:] == [getattr(cls, f).offset for f in fields]
+
+
 @pytest.mark.parametrize("field,value", [
     ("num_envs", 0), ("agents_per_env", -1), ("grid_x", 0), ("grid_z", -3), ("width", 0), ("height", 20000),
     ("hfov_rad", 0.0), ("hfov_rad", 3.2), ("num_materials", 0), ("num_materials", 256), ("coarse_level", 2),
@@ -106,6 +122,8 @@ def test_null_arguments(lib):
     assert lib.mv_render_batch(None, None, None, None, None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_fetch_observations(None, None, None, 0, 1, None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_move_voxels(None, 1, None, None, None, None, 0, None) == binding.MV_ERR_ARG
+    assert lib.mv_draw_bars(None, None, None, None, 0, None) == binding.MV_ERR_ARG
+    assert lib.mv_draw_overlay(None, None, None, 1, None, 0, 0, None) == binding.MV_ERR_ARG
     assert lib.mv_step(None, None, None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_step(None, C.byref(binding.MvStepInputs()), None, None, None) == binding.MV_ERR_ARG
     assert lib.mv_host_alloc(None, 16) == binding.MV_ERR_ARG

@@ -805,6 +805,88 @@ def test_active_mask_and_indicator_bars(lib, orc):
     assert e.value.code == binding.MV_ERR_ARG
 
 
+def test_overlay_of_primitives_equals_the_oracle(lib, orc):
+    """mv_draw_overlay against the oracle's overlay, byte for byte over the whole colour tensor: random lists of
+    solid rectangles and gauges that overlap, values from the device and from the host, inactive environments left
+    alone; the depth is not touched; one rightward gauge is the indicator bar; bad lists are refused."""
+    wl = synth.generate(1, num_envs=16)
+    spec = wl.spec
+    W, H = spec.width, spec.height
+    rng = np.random.default_rng(4711)
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
+    run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0])
+    active = (rng.random(spec.num_envs) < 0.7).astype(np.uint8)
+    active[0], active[1] = 0, 1
+    obs_active = np.repeat(active.astype(bool), spec.agents_per_env)
+
+    def random_list(n, per_obs):
+        rects = []
+        for _ in range(n):
+            w, h = int(rng.integers(1, W + 1)), int(rng.integers(1, H + 1))
+            if rng.random() < 0.5:
+                w, h = min(w, 24), min(h, 10)
+            x, y = int(rng.integers(0, W - w + 1)), int(rng.integers(0, H - h + 1))
+            kind = int(rng.integers(0, 3)) if per_obs > 0 else 0
+            rects.append((x, y, w, h, tuple(int(v) for v in rng.integers(0, 256, 3)), kind,
+                          tuple(int(v) for v in rng.integers(0, 256, 3)), int(rng.integers(0, max(per_obs, 1)))))
+        return rects
+
+    cases = [(1, 0), (1, 1), (5, 3), (12, 8), (32, 2), (7, 0)]
+    for case, (n, per_obs) in enumerate(cases):
+        rects = random_list(n, per_obs)
+        values = None
+        if per_obs > 0:
+            values = rng.uniform(-0.3, 1.3, size=(spec.num_obs, per_obs)).astype(np.float32)
+            values[:4, 0] = [0.0, 1.0, 0.5, 0.25]
+        for src in ("device", "host"):
+            run.batch.set_active(active if case % 2 == 0 else None, stream=_stream())
+            run.render()                                      # poisons the outputs first
+            before = run.numpy()
+            given = None if values is None else (torch.from_numpy(values).cuda() if src == "device" else values)
+            run.batch.draw_overlay(run.rgb, rects, given, stream=_stream())
+            torch.cuda.synchronize()
+            g = run.numpy()
+            want = before.rgb.copy()
+            ob.draw_overlay(want, rects, values, active=active if case % 2 == 0 else None)
+            np.testing.assert_array_equal(g.rgb, want, err_msg=f"case {case} ({n} primitives, {per_obs} values, {src})")
+            np.testing.assert_array_equal(g.depth.view(np.uint32), before.depth.view(np.uint32))
+            if case % 2 == 0:
+                assert (g.rgb[~obs_active] == 7).all()
+            covered = np.zeros((H, W), bool)
+            for x, y, w, h, *_ in rects:
+                covered[y:y + h, x:x + w] = True
+            np.testing.assert_array_equal(g.rgb[:, ~covered], before.rgb[:, ~covered])     # the render shows through
+    # one rightward gauge is the bar
+    run.batch.set_active(None)
+    fractions = rng.uniform(-0.2, 1.2, size=spec.num_obs).astype(np.float32)
+    run.render()
+    run.batch.draw_bars(run.rgb, fractions, 8, 4, 100, 3, (255, 255, 0), (40, 40, 40), stream=_stream())
+    torch.cuda.synchronize()
+    with_bar = run.numpy().rgb.copy()
+    run.render()
+    run.batch.draw_overlay(run.rgb, [(8, 4, 100, 3, (255, 255, 0), binding.RECT_GAUGE_RIGHT, (40, 40, 40), 0)],
+                           fractions.reshape(-1, 1), stream=_stream())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.numpy().rgb, with_bar)
+    # refusals
+    ok = (0, 0, 4, 4, (1, 2, 3), 0, (0, 0, 0), 0)
+    for rects, values in (([(W - 3, 0, 4, 4, (0, 0, 0), 0, (0, 0, 0), 0)], None),              # sticks out
+                          ([(0, 0, 4, 4, (0, 0, 0), 3, (0, 0, 0), 0)], None),                  # unknown kind
+                          ([(0, 0, 4, 4, (0, 0, 0), 1, (0, 0, 0), 0)], None),                  # a gauge without values
+                          ([(0, 0, 4, 4, (0, 0, 0), 2, (0, 0, 0), 2)], np.zeros((spec.num_obs, 2), np.float32)),
+                          ([ok] * 33, None),                                                   # too many primitives
+                          ([ok], np.zeros((spec.num_obs, 9), np.float32)),                     # too many values
+                          ([], None)):
+        with pytest.raises(binding.MvError) as e:
+            run.batch.draw_overlay(run.rgb, rects, values)
+        assert e.value.code == binding.MV_ERR_ARG, (rects[:1], e.value.code)
+    bad = np.zeros((spec.num_obs, 1), np.float32)
+    bad[5, 0] = np.nan
+    with pytest.raises(binding.MvError) as e:
+        run.batch.draw_overlay(run.rgb, [(0, 0, 4, 4, (0, 0, 0), 1, (0, 0, 0), 0)], bad)
+    assert e.value.code == binding.MV_ERR_ARG
+
+
 def test_single_call_step_against_the_oracle(lib, orc):
     """mv_step = edits + cameras + finished-episode flags + render + bar in one call, device inputs only:
     three steps of the dynamic workload against the oracle; frames of finished environments keep what the
