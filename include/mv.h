@@ -240,7 +240,7 @@ int mv_draw_overlay(mv_batch* batch, uint8_t* rgb, const mv_rect* rects, int32_t
  * voxel edits (mv_update_voxels), moves the cameras (mv_set_cameras), marks the environments whose
  * episode ended with this step as inactive (mv_set_active with the flags inverted), renders every other
  * environment (mv_render_batch without the aux outputs) and, if asked, paints the indicator bar
- * (mv_draw_bars).  Every pointer in mv_step_inputs is DEVICE memory on the batch's device and is not
+ * (mv_draw_bars) and then the overlay primitives (mv_draw_overlay).  Every pointer in mv_step_inputs is DEVICE memory on the batch's device and is not
  * validated; nothing is copied to the host, allocated or waited for, so the call can be captured in a
  * HIP graph.  The caller resets a finished environment by uploading its next world (mv_upload_worlds with
  * first_env, count) before the step in which it is no longer flagged.  The inactive set stays in force for
@@ -257,6 +257,10 @@ typedef struct {
     const uint8_t* done;           /* [N] non-zero = episode ended, do not render; NULL = render all   */
     const float*   bar_fraction;   /* [N*A] filled share of the bar; NULL = no bar                     */
     const mv_bar*  bar;            /* HOST pointer, read during the call; required if bar_fraction     */
+    const mv_rect* overlay;        /* HOST pointer to num_overlay primitives, painted after the bar     */
+    int32_t        num_overlay;    /* 0 = no overlay                                                    */
+    int32_t        overlay_values_per_obs;  /* 0..MV_MAX_OVERLAY_VALUES                                 */
+    const float*   overlay_values; /* [N*A, overlay_values_per_obs] gauge values; NULL if no gauge      */
 } mv_step_inputs;
 
 /* rgb, depth: as for mv_render_batch (device, caller-owned; frames of finished environments keep what

@@ -53,7 +53,9 @@ class MvStepInputs(C.Structure):
     """Mirror of ``mv_step_inputs``."""
     _fields_ = [("num_edits", C.c_int32), ("edit_env", C.c_void_p), ("edit_voxel", C.c_void_p),
                 ("edit_material", C.c_void_p), ("cams", C.c_void_p), ("self_voxel", C.c_void_p),
-                ("done", C.c_void_p), ("bar_fraction", C.c_void_p), ("bar", C.POINTER(MvBar))]
+                ("done", C.c_void_p), ("bar_fraction", C.c_void_p), ("bar", C.POINTER(MvBar)),
+                ("overlay", C.POINTER(MvRect)), ("num_overlay", C.c_int32), ("overlay_values_per_obs", C.c_int32),
+                ("overlay_values", C.c_void_p)]
 
 
 class MvError(RuntimeError):
@@ -165,6 +167,17 @@ def render_worlds_noalloc(cfg: MvConfig, voxels, palette, cams, self_voxel, rgb,
                                                    _as_ptr(self_voxel), _as_ptr(rgb), _as_ptr(depth), stream))
 
 
+def _pack_rects(rects):
+    """A ctypes array of ``mv_rect`` from (x, y, width, height, rgb, kind, rest_rgb, value_index) tuples."""
+    packed = (MvRect * max(len(rects), 1))()
+    for k, (x, y, width, height, colour, kind, rest, value_index) in enumerate(rects):
+        q = packed[k]
+        q.x, q.y, q.width, q.height, q.kind, q.value_index = x, y, width, height, kind, value_index
+        q.rgb[:] = [int(v) for v in colour]
+        q.rest_rgb[:] = [int(v) for v in rest]
+    return packed
+
+
 class PinnedBuffer:
     """Page-locked host memory from ``mv_host_alloc``; ``array(dtype, shape)`` views it as a NumPy array."""
 
@@ -258,21 +271,16 @@ class Batch:
     def draw_overlay(self, rgb, rects, values=None, stream: int = 0) -> None:
         """``rects``: a sequence of (x, y, width, height, rgb, kind, rest_rgb, value_index), painted in this order;
         ``values``: f32[N*A, k] as a torch CUDA tensor or a host array, or None when no primitive is a gauge."""
-        packed = (MvRect * max(len(rects), 1))()
-        for k, (x, y, width, height, colour, kind, rest, value_index) in enumerate(rects):
-            q = packed[k]
-            q.x, q.y, q.width, q.height, q.kind, q.value_index = x, y, width, height, kind, value_index
-            q.rgb[:] = [int(v) for v in colour]
-            q.rest_rgb[:] = [int(v) for v in rest]
+        packed = _pack_rects(rects)
         per_obs = 0 if values is None else int(values.shape[1])
         _check(load_library().mv_draw_overlay(self._h, _as_ptr(rgb), packed, len(rects), _as_ptr(values), per_obs,
                                               1 if values is not None and _is_device(values) else 0, stream))
 
     def step(self, cams, rgb, depth, edits=None, self_voxel=None, done=None, bar_fraction=None, bar=None,
-             stream: int = 0) -> None:
+             overlay=None, overlay_values=None, stream: int = 0) -> None:
         """One whole step from device tensors: ``edits`` = (env i32[n], voxel i32[n], material u8[n]) or None,
         ``done`` u8[N] or None, ``bar`` = dict(x, y, width, height, fill_rgb, empty_rgb) with ``bar_fraction``
-        f32[N*A]."""
+        f32[N*A], ``overlay`` = primitives as for ``draw_overlay`` with ``overlay_values`` f32[N*A, k]."""
         inp = MvStepInputs()
         if edits is not None:
             env, voxel, material = edits
@@ -289,6 +297,11 @@ class Batch:
             c_bar.fill_rgb[:] = [int(v) for v in bar["fill_rgb"]]
             c_bar.empty_rgb[:] = [int(v) for v in bar["empty_rgb"]]
             inp.bar = C.pointer(c_bar)
+        if overlay:
+            packed = _pack_rects(overlay)
+            inp.overlay, inp.num_overlay = packed, len(overlay)
+            if overlay_values is not None:
+                inp.overlay_values, inp.overlay_values_per_obs = _as_ptr(overlay_values), int(overlay_values.shape[1])
         _check(load_library().mv_step(self._h, C.byref(inp), _as_ptr(rgb), _as_ptr(depth), stream))
 
     def fetch_observations(self, rgb_dev, depth_dev, first_obs: int, count: int, rgb_host, depth_host,

@@ -648,6 +648,8 @@ int mv_step(mv_batch* b, const mv_step_inputs* in, uint8_t* rgb, float* depth, v
         return fail(MV_ERR_ARG, "mv_step: %d edits without their arrays", in->num_edits);
     if (!in->cams) return fail(MV_ERR_ARG, "mv_step: cams is null");
     if (in->bar_fraction && !in->bar) return fail(MV_ERR_ARG, "mv_step: bar_fraction without bar");
+    if (in->num_overlay < 0 || (in->num_overlay > 0 && !in->overlay))
+        return fail(MV_ERR_ARG, "mv_step: %d overlay primitives without their list", in->num_overlay);
     int rc = MV_OK;
     if (in->num_edits > 0)
         rc = mv_update_voxels(b, in->num_edits, in->edit_env, in->edit_voxel, in->edit_material, 1, hip_stream);
@@ -664,6 +666,9 @@ int mv_step(mv_batch* b, const mv_step_inputs* in, uint8_t* rgb, float* depth, v
     }
     if (rc == MV_OK) rc = mv_render_batch(b, rgb, depth, nullptr, nullptr, nullptr, hip_stream);
     if (rc == MV_OK && in->bar_fraction) rc = mv_draw_bars(b, rgb, in->bar_fraction, in->bar, 1, hip_stream);
+    if (rc == MV_OK && in->num_overlay > 0)
+        rc = mv_draw_overlay(b, rgb, in->overlay, in->num_overlay, in->overlay_values, in->overlay_values_per_obs, 1,
+                             hip_stream);
     return rc;
 }
 

@@ -55,7 +55,7 @@ def test_config_struct_layout_matches_header(lib):
     assert cfg.device == 0 and cfg.tiles_per_block == 0 and cfg.num_envs == 0
 
 
-@pytest.mark.parametrize("c_name,mirror", [("mv_bar", "MvBar"), ("mv_rect", "MvRect")])
+@pytest.mark.parametrize("c_name,mirror", [("mv_bar", "MvBar"), ("mv_rect", "MvRect"), ("mv_step_inputs", "MvStepInputs")])
 def test_overlay_struct_layouts_match_header(c_name, mirror):
     import subprocess, tempfile
     cls = getattr(binding, mirror)

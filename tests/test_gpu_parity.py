@@ -888,7 +888,7 @@ def test_overlay_of_primitives_equals_the_oracle(lib, orc):
 
 
 def test_single_call_step_against_the_oracle(lib, orc):
-    """mv_step = edits + cameras + finished-episode flags + render + bar in one call, device inputs only:
+    """mv_step = edits + cameras + finished-episode flags + render + bar + overlay in one call, device inputs only:
     three steps of the dynamic workload against the oracle; frames of finished environments keep what the
     tensors held; the flags of one step do not leak into the next."""
     wl = synth.generate(1, num_envs=12)
@@ -898,6 +898,10 @@ def test_single_call_step_against_the_oracle(lib, orc):
     ob = _oracle_for(orc, spec, wl.voxels, wl.palette, wl.cameras[0])
     run = _gpu_for(spec, wl.voxels, wl.palette, wl.cameras[0], aux=False)
     bar = dict(x=4, y=2, width=64, height=2, fill_rgb=(0, 255, 0), empty_rgb=(10, 10, 10))
+    # overlay: a frame part over the bar's right end, an upward gauge, and a mark on top of the gauge
+    overlay = [(60, 1, 12, 5, (200, 200, 0), binding.RECT_SOLID, (0, 0, 0), 0),
+               (100, 20, 6, 40, (255, 0, 0), binding.RECT_GAUGE_UP, (30, 30, 30), 1),
+               (100, 38, 6, 2, (255, 255, 255), binding.RECT_SOLID, (0, 0, 0), 0)]
     vox = wl.voxels.copy()
     for step in range(3):
         # this step's edits: a few voxels per environment set or cleared (one edit per voxel)
@@ -918,11 +922,17 @@ def test_single_call_step_against_the_oracle(lib, orc):
         active = np.ones(spec.num_envs, np.uint8) if done is None else (done == 0).astype(np.uint8)
         want_rgb = ref.rgb.copy()
         ob.draw_bars(want_rgb, fractions, active=active, **bar)
+        gauges = rng.uniform(-0.1, 1.1, size=(spec.num_obs, 2)).astype(np.float32)
+        with_overlay = step != 0
+        if with_overlay:
+            ob.draw_overlay(want_rgb, overlay, gauges, active=active)
         run.rgb.fill_(7)
         run.depth.fill_(-1.0)
         dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
         run.batch.step(dev(cams), run.rgb, run.depth, edits=(dev(env), dev(idx), dev(mat)), self_voxel=dev(selfv),
-                       done=dev(done), bar_fraction=dev(fractions), bar=bar, stream=_stream())
+                       done=dev(done), bar_fraction=dev(fractions), bar=bar,
+                       overlay=overlay if with_overlay else None, overlay_values=dev(gauges) if with_overlay else None,
+                       stream=_stream())
         torch.cuda.synchronize()
         rgb, depth = run.rgb.cpu().numpy(), run.depth.cpu().numpy()
         obs_active = np.repeat(active.astype(bool), spec.agents_per_env)
@@ -934,6 +944,9 @@ def test_single_call_step_against_the_oracle(lib, orc):
         assert (np.abs(depth - ref.depth)[ok] <= 1e-4 * np.abs(ref.depth)[ok]).all(), f"step {step}"
         assert (np.abs(rgb.astype(int) - want_rgb.astype(int)).max(axis=-1)[ok] <= 1).all(), f"step {step}"
         np.testing.assert_array_equal(rgb[obs_active][:, 2:4, 4:68], want_rgb[obs_active][:, 2:4, 4:68])
+        if with_overlay:
+            np.testing.assert_array_equal(rgb[obs_active][:, 1:6, 60:72], want_rgb[obs_active][:, 1:6, 60:72])
+            np.testing.assert_array_equal(rgb[obs_active][:, 20:60, 100:106], want_rgb[obs_active][:, 20:60, 100:106])
         assert ok.mean() > 0.5
     # without edits, flags and bar the call is cameras + render
     run.batch.step(torch.from_numpy(wl.cameras[0]).cuda(), run.rgb, run.depth, stream=_stream())
