@@ -726,6 +726,25 @@ def test_largest_grid_the_lds_plan_takes(lib, orc):
     parity.compare(run.numpy(), ob.render(threads=4), label="128x128x32 grid")
 
 
+@pytest.mark.parametrize("W,H", [(1920, 1080), (16384, 8), (8, 4096), (8, 16384)])
+def test_largest_images(lib, orc, W, H):
+    """Images far larger than the paper's 128x72, up to the largest width and height a configuration may name:
+    thousands of tiles per observation, strips much shorter than an observation, pixel scalars and row records that
+    fill most of a workgroup's LDS.  Either the batch is refused at creation for lack of LDS (MV_ERR_CAPACITY, nothing
+    half-made) or every pixel is held to the parity rule."""
+    wl = synth.generate(1, num_envs=2)
+    spec = _mini_spec(2, 1, wl.spec.grid, W, H, wl.spec.num_materials)
+    cams = np.ascontiguousarray(wl.cameras[0][::wl.spec.agents_per_env][:2])
+    try:
+        run = _gpu_for(spec, wl.voxels, wl.palette, cams)
+    except binding.MvError as e:
+        assert e.code == binding.MV_ERR_CAPACITY and H > 4096, (W, H, e.code, str(e))
+        return
+    run.render()
+    ob = _oracle_for(orc, spec, wl.voxels, wl.palette, cams)
+    parity.compare(run.numpy(), ob.render(threads=8), label=f"{W}x{H} image")
+
+
 def test_fetch_observations_into_pinned_and_pageable_memory(lib):
     """The device-to-host copy of a range of observations equals what the device tensors hold, for pinned
     memory from the library and for ordinary NumPy arrays, and rejects ranges outside the batch."""
