@@ -998,6 +998,12 @@ def test_step_replays_from_a_hip_graph(lib, orc):
     env_in = torch.full((max_edits,), -1, dtype=torch.int32, device="cuda")        # -1: dropped by the kernel
     idx_in = torch.zeros(max_edits, dtype=torch.int32, device="cuda")
     mat_in = torch.zeros(max_edits, dtype=torch.uint8, device="cuda")
+    # an overlay in the captured step as well: the list is read at capture time, the gauge values at every replay
+    overlay = [(2, 2, 40, 3, (0, 255, 0), binding.RECT_GAUGE_RIGHT, (20, 20, 20), 0),
+               (120, 10, 4, 50, (255, 0, 0), binding.RECT_GAUGE_UP, (20, 20, 20), 1),
+               (30, 1, 6, 5, (250, 250, 250), binding.RECT_SOLID, (0, 0, 0), 0)]
+    gauges_in = torch.zeros((spec.num_obs, 2), dtype=torch.float32, device="cuda")
+    gauge_rng = np.random.default_rng(77)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
@@ -1007,7 +1013,8 @@ def test_step_replays_from_a_hip_graph(lib, orc):
         with torch.cuda.graph(graph, stream=side):
             st = torch.cuda.current_stream().cuda_stream
             # the single-call form of the step; the eager path below uses the separate calls
-            batch.step(cams_in, run_g.rgb, run_g.depth, edits=(env_in, idx_in, mat_in), self_voxel=self_in, stream=st)
+            batch.step(cams_in, run_g.rgb, run_g.depth, edits=(env_in, idx_in, mat_in), self_voxel=self_in,
+                       overlay=overlay, overlay_values=gauges_in, stream=st)
     torch.cuda.synchronize()
     for step in range(1, 5):
         prev = vox
@@ -1019,6 +1026,8 @@ def test_step_replays_from_a_hip_graph(lib, orc):
                             stream=_stream())
         eager.set_cameras(torch.from_numpy(cams).cuda(), torch.from_numpy(selfv).cuda(), stream=_stream())
         run_e.render()
+        gauges = torch.from_numpy(gauge_rng.uniform(-0.1, 1.1, size=(spec.num_obs, 2)).astype(np.float32)).cuda()
+        eager.draw_overlay(run_e.rgb, overlay, gauges, stream=_stream())
         # graph path: refresh the captured input buffers, replay
         env_in.fill_(-1)
         env_in[:env.size] = torch.from_numpy(env).cuda()
@@ -1026,6 +1035,7 @@ def test_step_replays_from_a_hip_graph(lib, orc):
         mat_in[:env.size] = torch.from_numpy(mat).cuda()
         cams_in.copy_(torch.from_numpy(cams).cuda())
         self_in.copy_(torch.from_numpy(selfv).cuda())
+        gauges_in.copy_(gauges)
         run_g.rgb.fill_(7); run_g.depth.fill_(-1.0)
         torch.cuda.synchronize()
         graph.replay()
@@ -1033,7 +1043,16 @@ def test_step_replays_from_a_hip_graph(lib, orc):
         assert torch.equal(run_g.rgb, run_e.rgb), step
         assert torch.equal(run_g.depth.view(torch.int32), run_e.depth.view(torch.int32)), step
     ob = _oracle_for(orc, spec, vox, wl.palette, cams, selfv)
-    parity.compare(run_g.numpy(), ob.render(threads=8), label="graph replay, last step")
+    ref = ob.render(threads=8)
+    g = run_g.numpy()
+    covered = np.zeros((spec.height, spec.width), bool)
+    for x, y, w, h, *_ in overlay:
+        covered[y:y + h, x:x + w] = True
+    want = ref.rgb.copy()
+    ob.draw_overlay(want, overlay, gauges.cpu().numpy())
+    np.testing.assert_array_equal(g.rgb[:, covered], want[:, covered])      # the primitives, byte for byte
+    g.rgb[:, covered] = ref.rgb[:, covered]                                 # and every other pixel under the parity rule
+    parity.compare(g, ref, label="graph replay, last step")
 
 
 # ------------------------------------------------------------------------------------------ the other render paths, at scale
