@@ -997,7 +997,9 @@ __device__ __forceinline__ Hit trace_rows(uint32_t classes_addr, float dx, float
 // quad_perm [1,2,3,3]
 __device__ __forceinline__ uint32_t next_in_quad(uint32_t v)
 {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xF9, 0xF, 0xF, false);
+    // (every lane of a quad is named by the permutation, so no lane falls back on the first operand: with the
+    // bound-control bit set the compiler need not initialise one)
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xF9, 0xF, 0xF, true);
 }
 
 // COARSE: with the optional second occupancy level (pairs of rows), row-scan grids only
@@ -1296,10 +1298,12 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const int last_material = p.materials_plus_one - 1;
 
     // a6 + a7 of a finished tile: material -> colour, then the stores.
-    auto shade_and_store = [&](int idx, int hit_face, float t, int material, uint32_t pix, bool active) {
+    auto shade_and_store = [&](int idx, int hit_face, float t, int material, uint32_t pix, bool active, auto trusted_face) {
         // branch-free: lanes that found nothing look up a valid entry as well and then take the miss values
         const bool hit = idx >= 0;
-        const uint32_t shaded = lut_lds[mad24s(min(hit_face, kNumFaces - 1), p.materials_plus_one, min(material, last_material))];
+        // (the row scan takes its face codes from the scan-class records: nothing to clamp)
+        const int face_row = decltype(trusted_face)::value ? hit_face : min(hit_face, kNumFaces - 1);
+        const uint32_t shaded = lut_lds[mad24s(face_row, p.materials_plus_one, min(material, last_material))];
         const uint32_t colour = hit ? shaded : p.sky_packed;
         const float depth = hit ? t : 0.0f;
         const int face = hit ? hit_face : 255;
@@ -1391,7 +1395,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                                   origin_in_grid, p.max_steps, -1, -1);
             }
 
-            if (pending) shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
+            if (pending) shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active, rows_only_tag);
             pend_idx = h.idx; pend_face = h.face; pend_t = h.t;
             pend_pix = pix;
             pend_active = active;
@@ -1399,7 +1403,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         }
         if (pending) {
             const uint8_t pend_material = vox_env[min((uint32_t)pend_idx, last_voxel)];
-            shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active);
+            shade_and_store(pend_idx, pend_face, pend_t, pend_material, pend_pix, pend_active, rows_only_tag);
         }
     };
     __builtin_amdgcn_s_setprio(0);
