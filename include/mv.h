@@ -107,7 +107,15 @@ int mv_create_batch(const mv_config* cfg, mv_batch** out);
  * Packs occupancy bits and re-shades the colour tables on `stream`.  Host data is validated
  * (material id > num_materials -> MV_ERR_RANGE, nothing is changed); device data is not, ids
  * above num_materials are clamped to num_materials when shading.
- * Errors: MV_ERR_ARG, MV_ERR_RANGE, MV_ERR_HIP. */
+ * src_is_device == MV_SRC_DEVICE_BORROWED (a simulator that keeps its worlds on the GPU, paper Sec. 3.2): the
+ * material ids are NOT copied.  The call must name every environment (first_env 0, count N); the occupancy
+ * bits are packed from the caller's array, and every render up to the next mv_upload_worlds reads the material
+ * of a hit voxel from that array, which the caller keeps alive and does not change meanwhile (to change it, change it
+ * and call again: that re-packs, still without a copy).  While the batch borrows, mv_update_voxels, mv_move_voxels,
+ * the edits of mv_step and uploads of part of the environments return MV_ERR_STATE; an upload of all environments
+ * with src_is_device 0 or 1 ends the borrowing.  The palette is copied as always.
+ * Errors: MV_ERR_ARG, MV_ERR_RANGE, MV_ERR_STATE, MV_ERR_HIP. */
+#define MV_SRC_DEVICE_BORROWED 2
 int mv_upload_worlds(mv_batch* batch, int32_t first_env, int32_t count, const uint8_t* voxels,
                      const uint8_t* palette, int32_t src_is_device, void* hip_stream);
 

@@ -47,6 +47,7 @@ class MvRect(C.Structure):
 
 
 RECT_SOLID, RECT_GAUGE_RIGHT, RECT_GAUGE_UP = 0, 1, 2
+SRC_DEVICE_BORROWED = 2
 
 
 class MvStepInputs(C.Structure):
@@ -214,16 +215,19 @@ class Batch:
         self.num_obs = num_envs * agents_per_env
 
     def upload_worlds(self, voxels, palette=None, first_env: int = 0, count: Optional[int] = None,
-                      stream: int = 0) -> None:
+                      stream: int = 0, borrow: bool = False) -> None:
         """``voxels`` u8[count,Z,Y,X] and ``palette`` u8[count,M+1,3]: both torch CUDA tensors or both
-        host arrays (NumPy / CPU tensors)."""
+        host arrays (NumPy / CPU tensors).  ``borrow``: the device tensor of all environments is not copied; the
+        batch reads material ids from it until the next upload (the caller keeps it alive and unchanged)."""
         if count is None:
             count = int(voxels.shape[0])
         dev = _is_device(voxels)
         if palette is not None and _is_device(palette) != dev:
             raise ValueError("voxels and palette must live in the same memory space")
+        if borrow and not dev:
+            raise ValueError("only a device tensor can be borrowed")
         _check(load_library().mv_upload_worlds(self._h, first_env, count, _as_ptr(voxels), _as_ptr(palette),
-                                               1 if dev else 0, stream))
+                                               SRC_DEVICE_BORROWED if borrow else (1 if dev else 0), stream))
 
     def update_voxels(self, env, voxel_index, material, stream: int = 0) -> None:
         """Sparse edits: ``env`` i32[count], ``voxel_index`` i32[count], ``material`` u8[count], all three

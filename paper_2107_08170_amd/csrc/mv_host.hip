@@ -66,6 +66,7 @@ struct mv_batch {
     float intensity[mv::kNumFaces] = {};
 
     uint8_t* d_vox = nullptr;
+    const uint8_t* borrowed_vox = nullptr;   // the caller's material array while the batch borrows it, else null
     uint64_t* d_bits = nullptr;
     int32_t* d_ztop = nullptr;
     uint8_t* d_palette = nullptr;
@@ -323,6 +324,13 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
     if (first_env < 0 || first_env > b->cfg.num_envs - count)
         return fail(MV_ERR_RANGE, "mv_upload_worlds: environments %d..%d outside 0..%d", first_env,
                     first_env + count - 1, b->cfg.num_envs - 1);
+    if (src_is_device < 0 || src_is_device > MV_SRC_DEVICE_BORROWED)
+        return fail(MV_ERR_ARG, "mv_upload_worlds: src_is_device = %d", src_is_device);
+    const bool whole = first_env == 0 && count == b->cfg.num_envs;
+    if (src_is_device == MV_SRC_DEVICE_BORROWED && !whole)
+        return fail(MV_ERR_ARG, "mv_upload_worlds: a borrowed array must hold all %d environments", b->cfg.num_envs);
+    if (b->borrowed_vox && !whole)
+        return fail(MV_ERR_STATE, "mv_upload_worlds: the batch borrows its material ids; upload all environments to end that");
     DeviceScope scope(b->cfg.device);
     if (!scope.ok()) return fail(MV_ERR_HIP, "mv_upload_worlds: cannot select device %d", b->cfg.device);
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -348,12 +356,18 @@ int mv_upload_worlds(mv_batch* b, int32_t first_env, int32_t count, const uint8_
         MV_HIP(mv::launch_pack(vox_dst, vox_dst, bits_dst, ztop_dst, count, b->layout, palette ? pal_dst : nullptr,
                                pal_dst, lut_dst, b->materials_plus_one, b->intensity,
                                mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
+    } else if (src_is_device == MV_SRC_DEVICE_BORROWED) {
+        // source and destination of the material copy are the caller's array: nothing is copied
+        MV_HIP(mv::launch_pack(voxels, const_cast<uint8_t*>(voxels), bits_dst, ztop_dst, count, b->layout, palette, pal_dst,
+                               lut_dst, b->materials_plus_one, b->intensity,
+                               mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
     } else {
         // one launch: material copy, bit rows, palette copy and colour tables
         MV_HIP(mv::launch_pack(voxels, vox_dst, bits_dst, ztop_dst, count, b->layout, palette, pal_dst, lut_dst,
                                b->materials_plus_one, b->intensity,
                                mv::HeightFeedback{ b->d_height, b->h_height_dev }, stream));
     }
+    b->borrowed_vox = src_is_device == MV_SRC_DEVICE_BORROWED ? voxels : nullptr;
 
     for (int e = first_env; e < first_env + count; ++e) {
         if (!b->env_has_grid[e]) { b->env_has_grid[e] = 1; ++b->envs_with_grid; }
@@ -369,6 +383,7 @@ int mv_update_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32
     if (count < 0) return fail(MV_ERR_ARG, "mv_update_voxels: negative count");
     if (count == 0) return MV_OK;
     if (!env || !voxel_index || !material) return fail(MV_ERR_ARG, "mv_update_voxels: null argument");
+    if (b->borrowed_vox) return fail(MV_ERR_STATE, "mv_update_voxels: the batch borrows its material ids from the caller");
     DeviceScope scope(b->cfg.device);
     if (!scope.ok()) return fail(MV_ERR_HIP, "mv_update_voxels: cannot select device %d", b->cfg.device);
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -420,6 +435,7 @@ int mv_move_voxels(mv_batch* b, int32_t count, const int32_t* env, const int32_t
     if (count < 0) return fail(MV_ERR_ARG, "mv_move_voxels: negative count");
     if (count == 0) return MV_OK;
     if (!env || !from_voxel || !to_voxel || !material) return fail(MV_ERR_ARG, "mv_move_voxels: null argument");
+    if (b->borrowed_vox) return fail(MV_ERR_STATE, "mv_move_voxels: the batch borrows its material ids from the caller");
     DeviceScope scope(b->cfg.device);
     if (!scope.ok()) return fail(MV_ERR_HIP, "mv_move_voxels: cannot select device %d", b->cfg.device);
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -540,7 +556,7 @@ int mv_render_batch(mv_batch* b, uint8_t* rgb, float* depth, uint8_t* aux_materi
     p.coarse_after = b->cfg.coarse_level != 0 ? mv::kCoarseAfterTurns : -1;
     p.heights = mv::HeightFeedback{ b->d_height, b->h_height_dev };
     p.active = b->all_active ? nullptr : b->d_active;
-    p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
+    p.bits = b->d_bits; p.ztop = b->d_ztop; p.vox = b->borrowed_vox ? b->borrowed_vox : b->d_vox; p.lut = b->d_lut; p.rec = b->d_rec; p.sx = b->d_sx; p.sy = b->d_sy;
     p.rgb = rgb; p.depth = depth; p.aux_material = aux_material; p.aux_hit = aux_hit_index; p.aux_face = aux_face;
     {
         const int rc = shape_render(p, b->cfg, b->layout, plan, "mv_render_batch");

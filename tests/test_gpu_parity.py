@@ -745,6 +745,56 @@ def test_largest_images(lib, orc, W, H):
     parity.compare(run.numpy(), ob.render(threads=8), label=f"{W}x{H} image")
 
 
+def test_borrowed_worlds_render_the_same_bits(lib, orc):
+    """mv_upload_worlds with MV_SRC_DEVICE_BORROWED: no material copy, the render reads the caller's device array.
+    The images equal those of a copying upload bit for bit; changing the array and uploading again re-packs; edits and
+    partial uploads are refused while the batch borrows, and a copying upload of all environments ends that."""
+    wl = synth.generate(3, num_envs=48)
+    spec = wl.spec
+    cams, selfv = wl.cameras[0], wl.self_voxel[0]
+    copied = _gpu_for(spec, wl.voxels, wl.palette, cams, self_voxel=selfv)
+    copied.render()
+    want = copied.numpy()
+    parity.compare(want, _oracle_for(orc, spec, wl.voxels, wl.palette, cams, selfv).render(threads=8), label="copied upload")
+    batch = binding.Batch(spec.num_envs, spec.agents_per_env, spec.grid, spec.num_materials, spec.width, spec.height)
+    own = torch.from_numpy(wl.voxels).cuda()                   # the simulator's own array
+    pal = torch.from_numpy(wl.palette).cuda()
+    batch.upload_worlds(own, pal, stream=_stream(), borrow=True)
+    batch.set_cameras(torch.from_numpy(cams).cuda(), torch.from_numpy(selfv).cuda(), stream=_stream())
+    run = GpuRender(batch, spec.width, spec.height, aux=True)
+    run.render()
+    g = run.numpy()
+    for name in ("rgb", "material", "hit_index", "face"):
+        np.testing.assert_array_equal(getattr(g, name), getattr(want, name), err_msg=name)
+    np.testing.assert_array_equal(g.depth.view(np.uint32), want.depth.view(np.uint32))
+    # refused while borrowing
+    one = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for call in (lambda: batch.update_voxels(one, one, torch.ones(1, dtype=torch.uint8, device="cuda")),
+                 lambda: batch.move_voxels(one, one, one + 1, torch.ones(1, dtype=torch.uint8, device="cuda")),
+                 lambda: batch.upload_worlds(own[:4], pal[:4], first_env=0, count=4, stream=_stream())):
+        with pytest.raises(binding.MvError) as e:
+            call()
+        assert e.value.code == binding.MV_ERR_STATE
+    with pytest.raises(binding.MvError) as e:
+        batch.upload_worlds(own[:4], pal[:4], first_env=0, count=4, stream=_stream(), borrow=True)
+    assert e.value.code == binding.MV_ERR_ARG
+    # the simulator moves on: the next step's worlds written into the same array, packed again without a copy
+    vox2, cams2, selfv2 = synth.dynamic_step(wl)
+    own.copy_(torch.from_numpy(vox2).cuda())
+    batch.upload_worlds(own, None, stream=_stream(), borrow=True)
+    batch.set_cameras(torch.from_numpy(cams2).cuda(), torch.from_numpy(selfv2).cuda(), stream=_stream())
+    run.render()
+    parity.compare(run.numpy(), _oracle_for(orc, spec, vox2, wl.palette, cams2, selfv2).render(threads=8), label="borrowed, next step")
+    # a copying upload ends the borrowing: the caller's array may change or go away
+    batch.upload_worlds(own, None, stream=_stream())
+    torch.cuda.synchronize()
+    own.zero_()
+    torch.cuda.synchronize()
+    run.render()
+    parity.compare(run.numpy(), _oracle_for(orc, spec, vox2, wl.palette, cams2, selfv2).render(threads=8), label="copied again")
+    batch.update_voxels(one, one, torch.ones(1, dtype=torch.uint8, device="cuda"))      # edits work again
+
+
 def test_fetch_observations_into_pinned_and_pageable_memory(lib):
     """The device-to-host copy of a range of observations equals what the device tensors hold, for pinned
     memory from the library and for ordinary NumPy arrays, and rejects ranges outside the batch."""
