@@ -174,8 +174,8 @@ static int shape_render(mv::RenderParams& p, const mv_config& cfg, const mv::Gri
     p.threads = plan.threads;
     p.W = cfg.width; p.H = cfg.height; p.A = cfg.agents_per_env;
     p.materials_plus_one = (cfg.num_materials + 1);
-    p.tiles_x = (p.W + mv::kTile - 1) / mv::kTile;
-    const int tiles_y = (p.H + mv::kTile - 1) / mv::kTile;
+    p.tiles_x = (p.W + mv::kTileW - 1) / mv::kTileW;
+    const int tiles_y = (p.H + mv::kTileH - 1) / mv::kTileH;
     p.tiles_per_obs = p.tiles_x * tiles_y;
     int tpb = cfg.tiles_per_block;
     int tpb_tail = 0;                                   // 0: no shorter strips at the end of an XCD's work

@@ -1279,7 +1279,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int waves = threads >> 6;
     const int lane = threadIdx.x & 63;
-    const int lx = lane & 7, ly = lane >> 3, quad = lane & 3;
+    const int lx = lane % kTileW, ly = lane / kTileW, quad = lane & 3;
     const int lane_pix = ly * p.W + lx;
     const float* sx_lane = lds_sx + lx;
     const RowRecord* rowrec_lane = lds_rowrec + ly;
@@ -1360,11 +1360,11 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             RowRecord rr;
             uint32_t pix;
             if (PACKED) {
-                sx = sx_lane[tx * kTile];
-                rr = rowrec_lane[ty * kTile];
-                pix = (uint32_t)(lane_pix + (ty * p.W + tx) * kTile);
+                sx = sx_lane[tx * kTileW];
+                rr = rowrec_lane[ty * kTileH];
+                pix = (uint32_t)(lane_pix + ty * kTileH * p.W + tx * kTileW);
             } else {
-                const int col = tx * kTile + lx, row = ty * kTile + ly;
+                const int col = tx * kTileW + lx, row = ty * kTileH + ly;
                 active = col < p.W && row < p.H;
                 const int ccol = min(col, p.W - 1), crow = min(row, p.H - 1);
                 sx = lds_sx[ccol];
@@ -1541,7 +1541,7 @@ hipError_t launch_render(const RenderParams& p, size_t lds_bytes, hipStream_t st
 {
     const bool aux = p.aux_material || p.aux_hit || p.aux_face;
     // dword colour stores and unclamped tiles need whole 8x8 tiles and a 4-byte aligned colour tensor
-    const bool packed = (p.W % kTile == 0) && (p.H % kTile == 0) && ((reinterpret_cast<uintptr_t>(p.rgb) & 3) == 0);
+    const bool packed = (p.W % kTileW == 0) && (p.H % kTileH == 0) && ((reinterpret_cast<uintptr_t>(p.rgb) & 3) == 0);
     const bool fast = p.g.fast != 0;
     dim3 grid(p.blocks_per_xcd * kXcds), block(p.threads);
 #define MV_LAUNCH(A, P, F) hipLaunchKernelGGL((render_kernel<A, P, F>), grid, block, lds_bytes, stream, p)
