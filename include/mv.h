@@ -339,11 +339,31 @@ const char* mv_last_error(void);
  *                        kernels, without synchronising); an environment that needs more is traced
  *                        through device memory instead, with identical results.  This call fixes the number
  *                        (1..Z) so that tests can reach that path; 0 returns to the automatic choice.
- *                        Errors: MV_ERR_ARG, MV_ERR_RANGE. */
+ *                        Errors: MV_ERR_ARG, MV_ERR_RANGE.
+ *   mv_debug_launch_shape : how a render of this configuration with `staged_layers` layers on chip (0 = all Z)
+ *                        is laid out, computed on the host without touching a GPU: *shape receives the LDS bytes and
+ *                        threads of a workgroup and the work list (workgroup b of the launch belongs to XCD b mod 8
+ *                        and is number s = b div 8 there; an XCD renders the observations x*obs_per_xcd ..
+ *                        (x+1)*obs_per_xcd-1 that exist; s < obs_body_per_xcd*blocks_per_obs: observation
+ *                        s div blocks_per_obs of the range, strip s mod blocks_per_obs of tiles_per_block tiles;
+ *                        later workgroups cut the remaining observations into blocks_per_obs_tail strips of
+ *                        tiles_per_block_tail tiles; a strip is tiles strip*t .. min((strip+1)*t, tiles_per_obs)-1
+ *                        of the observation's tiles_x-wide, row-major grid of 8x8-pixel tiles; where an observation has
+ *                        an even number of strips, which workgroup takes which of them is rotated by a hash of the
+ *                        observation index).
+ *                        Errors: those of mv_create_batch for the configuration. */
 int mv_debug_occupancy(mv_batch* batch, int32_t env, const uint64_t** x_rows, int32_t* x_row_words,
                        const uint64_t** y_rows, int32_t* y_row_words, const int32_t** top_layer);
 int mv_debug_camera_records(mv_batch* batch, const void** records);
 int mv_debug_set_staged_layers(mv_batch* batch, int32_t layers);
+typedef struct {
+    int32_t lds_bytes, threads;
+    int32_t tiles_x, tiles_per_obs;
+    int32_t tiles_per_block, blocks_per_obs, tiles_per_block_tail, blocks_per_obs_tail;
+    int32_t num_obs, obs_per_xcd, obs_body_per_xcd;
+    uint32_t blocks_per_xcd;       /* the launch has 8 * blocks_per_xcd workgroups */
+} mv_launch_shape;
+int mv_debug_launch_shape(const mv_config* cfg, int32_t staged_layers, mv_launch_shape* shape);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,7 @@ FACE_INSIDE, FACE_MISS = 6, 255
 EXPORTS = ("mv_default_config", "mv_create_batch", "mv_upload_worlds", "mv_update_voxels", "mv_set_cameras",
            "mv_render_batch", "mv_set_active", "mv_draw_bars", "mv_draw_overlay", "mv_step", "mv_host_alloc", "mv_host_free",
            "mv_fetch_observations", "mv_destroy", "mv_last_error", "mv_debug_occupancy", "mv_debug_camera_records",
-           "mv_debug_set_staged_layers", "mv_render_worlds_noalloc", "mv_move_voxels")
+           "mv_debug_set_staged_layers", "mv_debug_launch_shape", "mv_render_worlds_noalloc", "mv_move_voxels")
 NOALLOC_SCRATCH_BYTES = 8 << 20
 
 
@@ -48,6 +48,14 @@ class MvRect(C.Structure):
 
 RECT_SOLID, RECT_GAUGE_RIGHT, RECT_GAUGE_UP = 0, 1, 2
 SRC_DEVICE_BORROWED = 2
+
+
+class MvLaunchShape(C.Structure):
+    """Mirror of ``mv_launch_shape``."""
+    _fields_ = [(name, C.c_int32) for name in ("lds_bytes", "threads", "tiles_x", "tiles_per_obs", "tiles_per_block",
+                                               "blocks_per_obs", "tiles_per_block_tail", "blocks_per_obs_tail",
+                                               "num_obs", "obs_per_xcd", "obs_body_per_xcd")] + \
+               [("blocks_per_xcd", C.c_uint32)]
 
 
 class MvStepInputs(C.Structure):
@@ -90,6 +98,7 @@ def load_library():
     lib.mv_draw_bars.argtypes = [vp, vp, vp, C.POINTER(MvBar), C.c_int32, vp]
     lib.mv_draw_overlay.argtypes = [vp, vp, C.POINTER(MvRect), C.c_int32, vp, C.c_int32, C.c_int32, vp]
     lib.mv_step.argtypes = [vp, C.POINTER(MvStepInputs), vp, vp, vp]
+    lib.mv_debug_launch_shape.argtypes = [C.POINTER(MvConfig), C.c_int32, C.POINTER(MvLaunchShape)]
     lib.mv_host_alloc.argtypes = [C.POINTER(vp), C.c_size_t]
     lib.mv_host_free.argtypes = [vp]
     lib.mv_host_free.restype = None
@@ -177,6 +186,13 @@ def _pack_rects(rects):
         q.rgb[:] = [int(v) for v in colour]
         q.rest_rgb[:] = [int(v) for v in rest]
     return packed
+
+
+def launch_shape(cfg: MvConfig, staged_layers: int = 0) -> MvLaunchShape:
+    """The launch layout of a render of ``cfg`` (host arithmetic only, no GPU needed)."""
+    shape = MvLaunchShape()
+    _check(load_library().mv_debug_launch_shape(C.byref(cfg), staged_layers, C.byref(shape)))
+    return shape
 
 
 class PinnedBuffer:

@@ -747,6 +747,29 @@ int mv_debug_occupancy(mv_batch* b, int32_t env, const uint64_t** x_rows, int32_
     return MV_OK;
 }
 
+int mv_debug_launch_shape(const mv_config* cfg, int32_t staged_layers, mv_launch_shape* shape)
+{
+    if (!cfg || !shape) return fail(MV_ERR_ARG, "mv_debug_launch_shape: null argument");
+    mv::GridLayout layout{};
+    mv::LdsPlan plan{};
+    const int rc = check_config(cfg, "mv_debug_launch_shape", &layout, &plan);
+    if (rc != MV_OK) return rc;
+    if (staged_layers < 0 || staged_layers > cfg->grid_z)
+        return fail(MV_ERR_RANGE, "mv_debug_launch_shape: %d layers outside 0..%d", staged_layers, cfg->grid_z);
+    if (staged_layers > 0)
+        plan = mv::plan_lds(layout, cfg->width, cfg->height, cfg->num_materials + 1, staged_layers, cfg->coarse_level != 0);
+    mv::RenderParams p{};
+    const int rc2 = shape_render(p, *cfg, layout, plan, "mv_debug_launch_shape");
+    if (rc2 != MV_OK) return rc2;
+    shape->lds_bytes = (int32_t)plan.bytes; shape->threads = plan.threads;
+    shape->tiles_x = p.tiles_x; shape->tiles_per_obs = p.tiles_per_obs;
+    shape->tiles_per_block = p.tiles_per_block; shape->blocks_per_obs = p.blocks_per_obs;
+    shape->tiles_per_block_tail = p.tiles_per_block_tail; shape->blocks_per_obs_tail = p.blocks_per_obs_tail;
+    shape->num_obs = p.num_obs; shape->obs_per_xcd = p.obs_per_xcd; shape->obs_body_per_xcd = p.obs_body_per_xcd;
+    shape->blocks_per_xcd = p.blocks_per_xcd;
+    return MV_OK;
+}
+
 int mv_debug_set_staged_layers(mv_batch* b, int32_t layers)
 {
     if (!b) return fail(MV_ERR_ARG, "mv_debug_set_staged_layers: null batch");

@@ -55,7 +55,8 @@ def test_config_struct_layout_matches_header(lib):
     assert cfg.device == 0 and cfg.tiles_per_block == 0 and cfg.num_envs == 0
 
 
-@pytest.mark.parametrize("c_name,mirror", [("mv_bar", "MvBar"), ("mv_rect", "MvRect"), ("mv_step_inputs", "MvStepInputs")])
+@pytest.mark.parametrize("c_name,mirror", [("mv_bar", "MvBar"), ("mv_rect", "MvRect"), ("mv_step_inputs", "MvStepInputs"),
+                                           ("mv_launch_shape", "MvLaunchShape")])
 def test_overlay_struct_layouts_match_header(c_name, mirror):
     import subprocess, tempfile
     cls = getattr(binding, mirror)
@@ -148,3 +149,77 @@ def test_product_package_does_not_touch_the_oracle():
         if f.endswith((".py", ".c", ".h")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2107_08170_amd" not in text and "mv.h" not in text.replace("mv_oracle.h", ""), f
+
+
+# ------------------------------------------------------------------------------------------ launch layout (host logic)
+def _work_list(shape):
+    """Replays the documented mapping of workgroups to (observation, tile range): for every workgroup of the launch
+    either nothing (a surplus workgroup) or one strip."""
+    out = []
+    for b in range(8 * shape.blocks_per_xcd):
+        xcd, seq = b % 8, b // 8
+        body = shape.obs_body_per_xcd * shape.blocks_per_obs
+        if seq < body:
+            local, part, tpb, strips = seq // shape.blocks_per_obs, seq % shape.blocks_per_obs, shape.tiles_per_block, shape.blocks_per_obs
+        else:
+            s2 = seq - body
+            local, part = shape.obs_body_per_xcd + s2 // shape.blocks_per_obs_tail, s2 % shape.blocks_per_obs_tail
+            tpb, strips = shape.tiles_per_block_tail, shape.blocks_per_obs_tail
+            if local >= shape.obs_per_xcd:
+                continue
+        obs = xcd * shape.obs_per_xcd + local
+        if obs >= shape.num_obs:
+            continue
+        begin = part * tpb
+        out.append((obs, begin, min(begin + tpb, shape.tiles_per_obs), strips))
+    return out
+
+
+@pytest.mark.parametrize("envs,agents,grid,image,staged", [
+    (4, 1, (16, 16, 8), (128, 72), 0), (256, 4, (40, 40, 16), (128, 72), 0), (4096, 2, (40, 40, 16), (128, 72), 10),
+    (1024, 4, (40, 40, 16), (128, 72), 10), (2048, 4, (64, 64, 32), (256, 144), 16), (1, 1, (1, 1, 1), (1, 1), 0),
+    (3, 5, (7, 5, 3), (33, 19), 0), (2, 1, (40, 40, 16), (1920, 1080), 0), (2, 1, (40, 40, 16), (16384, 8), 0),
+    (1000, 3, (64, 64, 6), (130, 70), 2), (17, 1, (128, 128, 32), (64, 40), 0), (9, 2, (96, 96, 16), (128, 72), 0),
+])
+def test_every_tile_of_every_observation_belongs_to_exactly_one_workgroup(lib, envs, agents, grid, image, staged):
+    """The launch layout, computed on the host: the strips of the work list cover every tile of every observation once,
+    nothing else and nothing twice; the workgroup fits the compute unit; the image tiling covers the image."""
+    cfg = binding.make_config(envs, agents, grid, 16, width=image[0], height=image[1])
+    shape = binding.launch_shape(cfg, staged)
+    assert shape.num_obs == envs * agents
+    assert shape.tiles_x == -(-image[0] // 8) and shape.tiles_per_obs == shape.tiles_x * -(-image[1] // 8)
+    assert 0 < shape.lds_bytes <= 160 * 1024 and shape.threads in (256, 512, 768, 1024)
+    assert shape.obs_per_xcd * 8 >= shape.num_obs and 0 <= shape.obs_body_per_xcd <= shape.obs_per_xcd
+    assert shape.tiles_per_block >= 1 and shape.blocks_per_obs * shape.tiles_per_block >= shape.tiles_per_obs
+    assert (shape.blocks_per_obs - 1) * shape.tiles_per_block < shape.tiles_per_obs          # no empty strip
+    assert shape.blocks_per_obs_tail * shape.tiles_per_block_tail >= shape.tiles_per_obs
+    assert (shape.blocks_per_obs_tail - 1) * shape.tiles_per_block_tail < shape.tiles_per_obs
+    covered = {}
+    for obs, begin, end, _ in _work_list(shape):
+        assert 0 <= begin < end <= shape.tiles_per_obs
+        spans = covered.setdefault(obs, [])
+        spans.append((begin, end))
+    assert sorted(covered) == list(range(shape.num_obs))
+    for obs, spans in covered.items():
+        spans.sort()
+        assert spans[0][0] == 0 and spans[-1][1] == shape.tiles_per_obs, obs
+        assert all(a[1] == b[0] for a, b in zip(spans, spans[1:])), (obs, spans[:4])
+
+
+def test_launch_shape_follows_the_staged_layers_and_rejects_what_create_rejects(lib):
+    cfg = binding.make_config(4096, 2, (40, 40, 16), 16)
+    full, low = binding.launch_shape(cfg, 0), binding.launch_shape(cfg, 10)
+    assert low.lds_bytes < full.lds_bytes                 # fewer layers on chip, smaller workgroups' share
+    assert full.lds_bytes - low.lds_bytes == 6 * 4 * 40 * 8      # four row arrays of 40 rows of 8 bytes per layer
+    assert low.threads * (160 * 1024 // low.lds_bytes) >= 2048 or low.threads == 1024        # the CU's 32 wave slots are filled
+    with pytest.raises(binding.MvError) as e:
+        binding.launch_shape(cfg, 17)
+    assert e.value.code == binding.MV_ERR_RANGE
+    bad = binding.make_config(4, 1, (40, 40, 16), 16, width=0)
+    with pytest.raises(binding.MvError) as e:
+        binding.launch_shape(bad)
+    assert e.value.code == binding.MV_ERR_ARG
+    huge = binding.make_config(4, 1, (4096, 4096, 8), 16)
+    with pytest.raises(binding.MvError) as e:
+        binding.launch_shape(huge)
+    assert e.value.code == binding.MV_ERR_CAPACITY
