@@ -108,6 +108,7 @@ hipError_t launch_pixel_scalars(float* sx, float* sy, int W, int H, hipStream_t 
 // dword by dword (non-zero bytes -> nibble with a carry trick and one dot product), and the y rows
 // are the 64x64 bit transpose of the x rows, done across lanes without memory.  Other grids: lane r
 // gathers row r cell by cell.  Rows leave as one coalesced store per 64 rows.
+// A layer of air (no byte set) skips LDS and the transpose: its rows are written as zero words.
 // ------------------------------------------------------------------------------------------
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -203,8 +204,13 @@ __device__ __forceinline__ void report_height(const HeightFeedback& fb, int top)
 }
 
 // kPackPrefetch = dwords of the next layer each lane keeps in flight: 8 covers layers up to 2 KiB (40x40), 16
-// layers up to 4 KiB (64x64); the deeper variant costs registers, so small layers keep the shallow one.
-template <int kPackPrefetch>
+// layers up to 4 KiB (64x64); the deeper variant costs registers, so small layers keep the shallow one.  (Two
+// layers in flight per wave change nothing, four are slower: the kernel moves its bytes at the rate of a plain
+// device copy as it is.)
+// kFastPath = the host has checked that layers are prefetched, 16-byte aligned and one word per row: the other
+// paths are then not compiled into the kernel (they cost it a third of its registers, and with them two of its
+// eight waves per SIMD).
+template <int kPackPrefetch, bool kFastPath>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ vox_dst,
                                                             uint64_t* __restrict__ bits_dst, int32_t* __restrict__ ztop_dst,
                                                             GridLayout g, int vec_ok, const uint8_t* __restrict__ pal_src,
@@ -212,41 +218,27 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
                                                             int materials_plus_one, Intensities I, HeightFeedback heights)
 {
     extern __shared__ __align__(16) uint8_t layer_lds[];   // one layer per wave, padded to 16 bytes
-    if (pal_src) {
-        // the environment's palette: private copy, and the colour table lut[face][material]
-        const uint8_t* ps = pal_src + (size_t)blockIdx.x * materials_plus_one * 3;
-        uint8_t* pd = pal_dst + (size_t)blockIdx.x * materials_plus_one * 3;
-        uint32_t* lut = lut_dst + (size_t)blockIdx.x * kNumFaces * materials_plus_one;
-        if (ps != pd)
-            for (int i = threadIdx.x; i < materials_plus_one * 3; i += kPackThreads) pd[i] = ps[i];
-        for (int i = threadIdx.x; i < kNumFaces * materials_plus_one; i += kPackThreads) {
-            const int face = i / materials_plus_one, m = i - face * materials_plus_one;
-            lut[i] = shade_entry(ps + 3 * m, I.v[face]);
-        }
-    }
     __shared__ int top_lds;
     const int env = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int waves = kPackThreads / 64;
-    const int X = g.X, Y = g.Y;
+    const int X = g.X, Y = g.Y, Z = g.Z;
     const int XY = X * Y;
     const int layer_stride = (XY + 15) & ~15;
     uint8_t* mine = layer_lds + (size_t)wave * layer_stride;
-    const size_t env_vox = (size_t)env * XY * g.Z;
+    const size_t env_vox = (size_t)env * XY * Z;
     const bool copy = (src != vox_dst);
     uint64_t* xrows = bits_dst + (size_t)env * g.env_words;
     uint64_t* yrows = xrows + g.xrow_words;
-    if (threadIdx.x == 0) top_lds = 0;
-    __syncthreads();
     int top = 0;
-    // a layer of up to kPackPrefetch*64 dwords is prefetched into registers while the previous one is packed
     const int n4 = XY >> 2;
-    const bool prefetch = vec_ok && n4 <= kPackPrefetch * 64;
-    const bool quick = g.fast && (X & 3) == 0 && XY >= 8 * Y;     // the x rows (8 B each) fit over the layer in LDS
-    const bool wide = vec_ok == 2;                  // layers and pointers are 16-byte aligned: four dwords per access
+    const bool prefetch = kFastPath || (vec_ok && n4 <= kPackPrefetch * 64);
+    const bool quick = kFastPath || (g.fast && (X & 3) == 0 && XY >= 8 * Y);     // the x rows (8 B each) fit over the layer in LDS
+    const bool wide = kFastPath || vec_ok == 2;     // layers and pointers are 16-byte aligned: four dwords per access
     const int n16 = XY >> 4;
     uint32_t pre[kPackPrefetch];
-    auto fetch_layer = [&](const uint8_t* layer) {
+    auto fetch_layer = [&](int k) {
+        const uint8_t* layer = src + env_vox + (size_t)k * XY;
         if (wide) {
             const u32x4* s16 = reinterpret_cast<const u32x4*>(layer);
 #pragma unroll
@@ -261,60 +253,26 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
             for (int u = 0; u < kPackPrefetch; ++u) pre[u] = (u * 64 + lane) < n4 ? __builtin_nontemporal_load(&s4[u * 64 + lane]) : 0u;
         }
     };
-    if (prefetch && wave < g.Z) fetch_layer(src + env_vox + (size_t)wave * XY);
+    if (prefetch && wave < Z) fetch_layer(wave);
 
-    for (int k = wave; k < g.Z; k += waves) {
-        const uint8_t* lsrc = src + env_vox + (size_t)k * XY;
-        uint8_t* ldst = vox_dst + env_vox + (size_t)k * XY;
-        if (prefetch) {
-            // The private material copy is only ever read at voxels whose occupancy bit is set (the hit
-            // voxel of a ray), so a layer without any solid voxel is not copied: its old bytes stay behind
-            // bits that are all zero.
-            uint32_t any = 0;
-#pragma unroll
-            for (int u = 0; u < kPackPrefetch; ++u) any |= pre[u];
-            const bool store_copy = copy && __ballot(any != 0) != 0;
-            if (wide) {
-                u32x4* d16 = reinterpret_cast<u32x4*>(ldst);
-                u32x4* m16 = reinterpret_cast<u32x4*>(mine);
-#pragma unroll
-                for (int u = 0; u < kPackPrefetch / 4; ++u) {
-                    const int b = u * 64 + lane;
-                    if (b < n16) {
-                        const u32x4 v = { pre[4 * u], pre[4 * u + 1], pre[4 * u + 2], pre[4 * u + 3] };
-                        m16[b] = v;
-                        if (store_copy) __builtin_nontemporal_store(v, &d16[b]);
-                    }
-                }
-            } else {
-                uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
-                uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
-#pragma unroll
-                for (int u = 0; u < kPackPrefetch; ++u) {
-                    const int b = u * 64 + lane;
-                    if (b < n4) {
-                        m4[b] = pre[u];
-                        if (store_copy) __builtin_nontemporal_store(pre[u], &d4[b]);
-                    }
-                }
-            }
-            if (k + waves < g.Z) fetch_layer(lsrc + (size_t)waves * XY);
-        } else if (vec_ok) {
-            const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc);
-            uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
-            uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
-            for (int b = lane; b < n4; b += 64) {
-                uint32_t v = s4[b];
-                m4[b] = v;
-                if (copy) d4[b] = v;
-            }
-        } else {
-            for (int b = lane; b < XY; b += 64) {
-                uint8_t m = lsrc[b];
-                mine[b] = m;
-                if (copy) ldst[b] = m;
-            }
+    // (after the first layers have been requested, so that the palette's trip to memory runs beside theirs)
+    if (pal_src) {
+        // the environment's palette: private copy, and the colour table lut[face][material]
+        const uint8_t* ps = pal_src + (size_t)blockIdx.x * materials_plus_one * 3;
+        uint8_t* pd = pal_dst + (size_t)blockIdx.x * materials_plus_one * 3;
+        uint32_t* lut = lut_dst + (size_t)blockIdx.x * kNumFaces * materials_plus_one;
+        if (ps != pd)
+            for (int i = threadIdx.x; i < materials_plus_one * 3; i += kPackThreads) pd[i] = ps[i];
+        for (int i = threadIdx.x; i < kNumFaces * materials_plus_one; i += kPackThreads) {
+            const int face = i / materials_plus_one, m = i - face * materials_plus_one;
+            lut[i] = shade_entry(ps + 3 * m, I.v[face]);
         }
+    }
+    if (threadIdx.x == 0) top_lds = 0;
+    __syncthreads();
+
+    // the rows of layer k from its bytes in this wave's LDS slot
+    auto rows_from_lds = [&](int k) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         uint64_t seen = 0;
@@ -339,26 +297,96 @@ __global__ __launch_bounds__(kPackThreads) void pack_kernel(const uint8_t* __res
             const uint64_t ybits = transpose_bits_across_lanes(lane < Y ? xbits : 0ull, lane);
             if (lane < X) yrows[(size_t)k * X + lane] = ybits;
         } else {
-        // x rows: row (k*Y + j), word w holds cells i = 64w .. 64w+63
-        for (int j0 = 0; j0 < Y; j0 += 64) {
-            const int j = min(j0 + lane, Y - 1);
-            for (int w = 0; w < g.rowwords_x; ++w) {
-                const uint64_t bits = gather_row_bits(mine + j * X + w * 64, 1, min(64, X - w * 64));
-                seen |= bits;
-                if (j0 + lane < Y) xrows[((size_t)k * Y + j) * g.rowwords_x + w] = bits;
+            // x rows: row (k*Y + j), word w holds cells i = 64w .. 64w+63
+            for (int j0 = 0; j0 < Y; j0 += 64) {
+                const int j = min(j0 + lane, Y - 1);
+                for (int w = 0; w < g.rowwords_x; ++w) {
+                    const uint64_t bits = gather_row_bits(mine + j * X + w * 64, 1, min(64, X - w * 64));
+                    seen |= bits;
+                    if (j0 + lane < Y) xrows[((size_t)k * Y + j) * g.rowwords_x + w] = bits;
+                }
             }
-        }
-        // y rows: row (k*X + i), word w holds cells j = 64w .. 64w+63
-        for (int i0 = 0; i0 < X; i0 += 64) {
-            const int i = min(i0 + lane, X - 1);
-            for (int w = 0; w < g.rowwords_y; ++w) {
-                const uint64_t bits = gather_row_bits(mine + (w * 64) * X + i, X, min(64, Y - w * 64));
-                if (i0 + lane < X) yrows[((size_t)k * X + i) * g.rowwords_y + w] = bits;
+            // y rows: row (k*X + i), word w holds cells j = 64w .. 64w+63
+            for (int i0 = 0; i0 < X; i0 += 64) {
+                const int i = min(i0 + lane, X - 1);
+                for (int w = 0; w < g.rowwords_y; ++w) {
+                    const uint64_t bits = gather_row_bits(mine + (w * 64) * X + i, X, min(64, Y - w * 64));
+                    if (i0 + lane < X) yrows[((size_t)k * X + i) * g.rowwords_y + w] = bits;
+                }
             }
-        }
         }
         if (__ballot(seen != 0) != 0) top = k + 1;
         __builtin_amdgcn_wave_barrier();
+    };
+
+    if (prefetch) {
+        for (int k = wave; k < Z; k += waves) {
+            uint8_t* ldst = vox_dst + env_vox + (size_t)k * XY;
+            // The private material copy is only ever read at voxels whose occupancy bit is set (the hit
+            // voxel of a ray), so a layer without any solid voxel is not copied: its old bytes stay behind
+            // bits that are all zero.
+            uint32_t any = 0;
+#pragma unroll
+            for (int u = 0; u < kPackPrefetch; ++u) any |= pre[u];
+            const bool solid = __ballot(any != 0) != 0;
+            if (!solid && quick) {
+                // a layer of air: its rows are zero words, and neither LDS nor the transpose is needed for that
+                if (k + waves < Z) fetch_layer(k + waves);
+                if (lane < Y) xrows[(size_t)k * Y + lane] = 0ull;
+                if (lane < X) yrows[(size_t)k * X + lane] = 0ull;
+                continue;
+            }
+            const bool store_copy = copy && solid;
+            if (wide) {
+                u32x4* d16 = reinterpret_cast<u32x4*>(ldst);
+                u32x4* m16 = reinterpret_cast<u32x4*>(mine);
+#pragma unroll
+                for (int u = 0; u < kPackPrefetch / 4; ++u) {
+                    const int b = u * 64 + lane;
+                    if (b < n16) {
+                        const u32x4 v = { pre[4 * u], pre[4 * u + 1], pre[4 * u + 2], pre[4 * u + 3] };
+                        m16[b] = v;
+                        if (store_copy) __builtin_nontemporal_store(v, &d16[b]);
+                    }
+                }
+            } else {
+                uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
+                uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
+#pragma unroll
+                for (int u = 0; u < kPackPrefetch; ++u) {
+                    const int b = u * 64 + lane;
+                    if (b < n4) {
+                        m4[b] = pre[u];
+                        if (store_copy) __builtin_nontemporal_store(pre[u], &d4[b]);
+                    }
+                }
+            }
+            // the next layer is requested as soon as the registers are free, and arrives while this one is packed
+            if (k + waves < Z) fetch_layer(k + waves);
+            rows_from_lds(k);
+        }
+    } else {
+        for (int k = wave; k < Z; k += waves) {
+            const uint8_t* lsrc = src + env_vox + (size_t)k * XY;
+            uint8_t* ldst = vox_dst + env_vox + (size_t)k * XY;
+            if (vec_ok) {
+                const uint32_t* s4 = reinterpret_cast<const uint32_t*>(lsrc);
+                uint32_t* d4 = reinterpret_cast<uint32_t*>(ldst);
+                uint32_t* m4 = reinterpret_cast<uint32_t*>(mine);
+                for (int b = lane; b < n4; b += 64) {
+                    uint32_t v = s4[b];
+                    m4[b] = v;
+                    if (copy) d4[b] = v;
+                }
+            } else {
+                for (int b = lane; b < XY; b += 64) {
+                    uint8_t m = lsrc[b];
+                    mine[b] = m;
+                    if (copy) ldst[b] = m;
+                }
+            }
+            rows_from_lds(k);
+        }
     }
     if (lane == 0) atomicMax(&top_lds, top);
     __syncthreads();
@@ -388,12 +416,19 @@ hipError_t launch_pack(const uint8_t* src, uint8_t* vox_dst, uint64_t* bits_dst,
                  ((reinterpret_cast<uintptr_t>(vox_dst) & 3) == 0);
     if (vec_ok && XY % 16 == 0 && ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(vox_dst)) & 15) == 0)
         vec_ok = 2;
-    if (XY / 4 <= 8 * 64)
-        hipLaunchKernelGGL(pack_kernel<8>, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
-                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I, heights);
-    else
-        hipLaunchKernelGGL(pack_kernel<16>, dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst, bits_dst, ztop_dst,
-                           g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I, heights);
+    const int X = g.X, Y = g.Y;
+    const bool quick = g.fast && (X & 3) == 0 && XY >= (size_t)8 * Y;
+    const bool deep = XY / 4 > 8 * 64;
+    const bool fast_path = vec_ok == 2 && quick && XY / 4 <= (size_t)(deep ? 16 : 8) * 64;
+#define MV_LAUNCH_PACK(PREFETCH, FASTPATH)                                                                              \
+    hipLaunchKernelGGL((pack_kernel<PREFETCH, FASTPATH>), dim3(count), dim3(kPackThreads), lds, stream, src, vox_dst,    \
+                       bits_dst, ztop_dst, g, vec_ok, pal_src, pal_dst, lut_dst, materials_plus_one, I, heights)
+    if (!deep) {
+        if (fast_path) MV_LAUNCH_PACK(8, true); else MV_LAUNCH_PACK(8, false);
+    } else {
+        if (fast_path) MV_LAUNCH_PACK(16, true); else MV_LAUNCH_PACK(16, false);
+    }
+#undef MV_LAUNCH_PACK
     return hipGetLastError();
 }
 
@@ -1527,12 +1562,12 @@ hipError_t prepare_kernels()
 #undef MV_SET
     // the pack kernel also has a few static words of LDS: its dynamic share must leave room for them
     const int pack_limit = (int)(kLdsBudget - kPackStaticLds);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_kernel<8>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                pack_limit);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_kernel<16>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                pack_limit);
+#define MV_SET(N, F)                                                                                              \
+    if (e == hipSuccess)                                                                                          \
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_kernel<N, F>),                                \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, pack_limit)
+    MV_SET(8, false); MV_SET(8, true); MV_SET(16, false); MV_SET(16, true);
+#undef MV_SET
     if (e == hipSuccess && device >= 0 && device < kMaxDevices) done[device].store(true, std::memory_order_release);
     return e;
 }
