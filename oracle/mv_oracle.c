@@ -328,7 +328,23 @@ static void trace_pixel(const mvo_batch* b, int32_t obs, int32_t row, int32_t co
             if (ta > t_near) { t_near = ta; entry_axis = a; }
             if (tb < t_far) t_far = tb;
         }
-        if (t_near > t_far || t_far < 0.0) return;
+        if (t_near > t_far || t_far < 0.0) {
+            /* The ray passes the whole grid by.  If it does so within a hair of the rim of the boundary face it
+               would have entered through, that is a tie like any grazed voxel edge (enter the voxel at the rim,
+               or miss everything): the margin is how far outside that face's rectangle the ray meets the face's
+               plane, the larger of its excesses along the two other axes. */
+            if (t_near > 0.0 && t_far >= 0.0 && entry_axis >= 0) {
+                double worst = 0.0;
+                for (int a = 0; a < 3; ++a) {
+                    if (a == entry_axis) continue;
+                    double q = P[a] + t_near * d[a];
+                    double excess = q < 0.0 ? -q : (q > (double)dim[a] ? q - (double)dim[a] : 0.0);
+                    if (excess > worst) worst = excess;
+                }
+                out->edge_margin = worst;
+            }
+            return;
+        }
         if (t_near > 0.0) t0 = t_near; else entry_axis = -1;
     }
 

@@ -630,6 +630,32 @@ def test_edge_margin_flags_ties_at_the_grid_boundary(orc):
     assert hit[3] == (1 * 8 + 6) * 8 + 7 and out.edge_margin[3, 0, 0] > 0.01   # clear hit
 
 
+def test_edge_margin_flags_a_ray_that_passes_the_grid_by_at_its_rim(orc):
+    """A camera outside the grid: the ray towards the vertical rim x = 0, y = 0 of the grid either enters the
+    corner voxel through the face x = 0 or passes the whole grid by.  Turned a hair either way it does one or the
+    other, and both are ties: the one that enters has a small margin from its first crossing, the one that passes
+    by must have one too (how far outside the face's rectangle it meets the plane x = 0).  A ray that passes
+    the rim at a distance keeps that distance as its margin, one that enters through the middle of the face a large one."""
+    grid = (4, 6, 3)
+    vox = np.zeros((3, 6, 4), np.uint8)
+    vox[1, 0, 0] = 1
+    pal = np.full((2, 3), 100, np.uint8)
+    P = (-2.0, 3.0, 1.5)
+    yaw = np.arctan2(-3.0, 2.0)                      # from (-2, 3) to the rim at (0, 0)
+    turned = yaw - 0.1                               # meets x = 0 at y = 3 + 2 tan(turned) < 0
+    cams = np.array([[*P, yaw + 2e-6, 0.0], [*P, yaw - 2e-6, 0.0], [*P, turned, 0.0], [*P, yaw + 0.5, 0.0]], np.float32)
+    b = orc.OracleBatch(1, 4, grid, 1, 1, 1)
+    b.upload_worlds(vox[None], pal[None])
+    b.set_cameras(cams)
+    out = b.render()
+    hit, m = out.hit_index[:, 0, 0], out.edge_margin[:, 0, 0]
+    assert hit[0] == (1 * 6 + 0) * 4 + 0 and hit[1] == -1, hit               # one enters, one passes by
+    assert m[0] < 5e-5 and m[1] < 5e-5, m
+    y_at_plane = 3.0 + 2.0 * np.tan(np.float64(np.float32(turned)))
+    assert hit[2] == -1 and abs(m[2] - (-y_at_plane)) < 1e-5, (m[2], y_at_plane)
+    assert hit[3] == -1 and m[3] > 0.02          # through the middle of the face and out again past the corner voxel
+
+
 def _margin_by_plane_enumeration(P, d, t_begin, t_end, dims):
     """The margin side channel written out from its definition, with no traversal: every integer plane of every
     axis that the ray reaches at a parameter t_begin <= t <= t_end (t > 0) is a crossing; at each crossing, the
@@ -658,7 +684,7 @@ def test_edge_margin_equals_plane_enumeration(orc):
     A margin that skips crossings, uses the wrong axes or the wrong parameter differs on almost every pixel."""
     rng = np.random.default_rng(77)
     w, h = 16, 9
-    checked = outside_checked = 0
+    checked = outside_checked = passed_by = 0
     for trial in range(8):
         grid = (int(rng.integers(3, 9)), int(rng.integers(3, 9)), int(rng.integers(2, 5)))
         vox, pal = synth.random_world(rng, 1, grid, float(rng.uniform(0.02, 0.2)), 3)
@@ -679,8 +705,19 @@ def test_edge_margin_equals_plane_enumeration(orc):
                     hi = [max((0.0 - P[k]) / d[k], (grid[k] - P[k]) / d[k]) for k in range(3) if d[k] != 0.0]
                     t_begin, t_exit = max(max(lo), 0.0), min(hi)
                     got = out.edge_margin[a, r, c]
-                    if t_begin > t_exit:                                     # never enters the grid: no crossing
-                        assert got == np.inf and out.hit_index[a, r, c] == -1
+                    if t_begin > t_exit:
+                        # never enters the grid: the margin is how far outside the rectangle of the boundary face
+                        # the ray meets that face's plane (the plane of the last slab it enters)
+                        assert out.hit_index[a, r, c] == -1
+                        if t_exit < 0.0:                                     # the grid lies behind the camera
+                            assert got == np.inf
+                            continue
+                        k_in = int(np.argmax([min((0.0 - P[k]) / d[k], (grid[k] - P[k]) / d[k]) if d[k] != 0.0
+                                              else -np.inf for k in range(3)]))
+                        q = P + t_begin * d
+                        want = max(max(-q[o], q[o] - grid[o], 0.0) for o in range(3) if o != k_in)
+                        assert abs(got - want) <= 1e-9, (trial, a, r, c, got, want)
+                        passed_by += 1
                         continue
                     if out.hit_index[a, r, c] >= 0:
                         if out.steps[a, r, c] == 0 and t_begin == 0.0:
@@ -695,7 +732,7 @@ def test_edge_margin_equals_plane_enumeration(orc):
                     assert abs(got - want) <= 1e-9, (trial, a, r, c, got, want)
                     checked += 1
                     outside_checked += int(t_begin > 0.0)
-    assert checked > 1500 and outside_checked > 300
+    assert checked > 1500 and outside_checked > 300 and passed_by > 100, (checked, outside_checked, passed_by)
 
 
 def test_edge_margin_flags_a_grazed_edge_inside_the_grid(orc):

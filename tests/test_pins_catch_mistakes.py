@@ -65,6 +65,8 @@ MISTAKES = [
     ("margin: crossing point from the wrong direction component", "mv_oracle.c", "double q = P[a] + t * d[a];", "double q = P[a] + t * d[axis];"),
     ("margin: only the last crossing counts", "mv_oracle.c", "if (m < out->edge_margin) out->edge_margin = m;", "out->edge_margin = m;"),
     ("margin: the crossing into the grid forgotten", "mv_oracle.c", "out->edge_margin = crossing_margin(P, d, t0, entry_axis);", ""),
+    ("margin: a ray that passes the whole grid by is never a tie", "mv_oracle.c", "out->edge_margin = worst;", ""),
+    ("margin: passing by takes the smaller excess", "mv_oracle.c", "if (excess > worst) worst = excess;", "if (worst == 0.0 || excess < worst) worst = excess;"),
     ("step counter counts every other crossing", "mv_oracle.c", "out->steps += 1;", "out->steps += (cell[axis] & 1);"),
     ("brute force keeps the farthest voxel", "mv_definition.c", "if (t_enter < best_t) {", "if (best_idx < 0 || t_enter > best_t) {"),
     ("brute force ignores rays leaving the slab", "mv_definition.c", "if (t_enter > t_leave || t_enter < 0.0) continue;", "if (t_enter < 0.0) continue;"),
@@ -99,6 +101,7 @@ def _battery(orc):
     yield lambda: pins.test_edge_margin_flags_ties_at_the_grid_boundary(orc)
     yield lambda: pins.test_edge_margin_equals_plane_enumeration(orc)
     yield lambda: pins.test_edge_margin_flags_a_grazed_edge_inside_the_grid(orc)
+    yield lambda: pins.test_edge_margin_flags_a_ray_that_passes_the_grid_by_at_its_rim(orc)
     yield lambda: pins.test_step_count_and_termination_bound(orc)
     yield lambda: pins.test_single_pixel_entry_point_equals_the_full_render(orc)
 
