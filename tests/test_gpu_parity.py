@@ -535,6 +535,72 @@ def test_randomized_entry_point_sequences(lib, orc):
         ob.close()
 
 
+def test_randomized_reupload_sequences(lib, orc):
+    """200 random configurations, five rounds each on one batch: new worlds that are lower, taller, empty in one
+    environment or have a layer of air in the middle, uploaded from device memory (copied), from host memory, borrowed
+    from a device array, or for a range of environments only; palettes replaced or kept; new cameras; every round
+    against the oracle.  (Layers of air are neither copied nor packed through LDS: stale material bytes stay behind
+    zero rows, and the staged layers follow the tallest world heard of.)"""
+    for seed in range(12000, 12200):
+        grid, W, H, N, A, M, vox, pal, cams, selfv, hfov = _random_configuration(seed)
+        rng = np.random.default_rng(seed + 7 * 10 ** 6)
+        X, Y, Z = grid
+        ob = orc.OracleBatch(N, A, grid, W, H, M, hfov_rad=hfov)
+        batch = binding.Batch(N, A, grid, M, W, H, hfov_rad=hfov)
+        run = GpuRender(batch, W, H, aux=True)
+        borrowed = []                                   # device arrays the batch may still read
+        cur_v, cur_p = vox.copy(), pal.copy()
+        for rnd in range(5):
+            first = rnd == 0
+            if first:
+                v2, p2 = cur_v, cur_p
+            else:
+                v2, p2 = synth.random_world(rng, N, grid, float(rng.choice([0.0, 0.05, 0.3, 0.8])), M)
+                v2[:, int(rng.integers(0, Z + 1)):] = 0
+                if rng.random() < 0.3:
+                    v2[int(rng.integers(0, N))] = 0
+                if rng.random() < 0.3 and Z > 2:
+                    v2[:, int(rng.integers(1, Z))] = 0
+            mode = int(rng.integers(0, 3 if first else 4))
+            new_pal = first or rng.random() < 0.5
+            where = f"seed {seed} round {rnd} mode {mode} grid {grid} image {W}x{H}"
+            if mode == 0:
+                batch.upload_worlds(torch.from_numpy(v2).cuda(), torch.from_numpy(p2).cuda() if new_pal else None, stream=_stream())
+            elif mode == 1:
+                batch.upload_worlds(v2, p2 if new_pal else None, stream=_stream())
+            elif mode == 2:
+                borrowed.append(torch.from_numpy(v2).cuda())
+                batch.upload_worlds(borrowed[-1], torch.from_numpy(p2).cuda() if new_pal else None, stream=_stream(), borrow=True)
+            else:
+                # a range of environments: the batch must own its grids for that, so a borrowing ends first
+                batch.upload_worlds(torch.from_numpy(cur_v).cuda(), None, stream=_stream())
+                e0 = int(rng.integers(0, N))
+                cnt = int(rng.integers(1, N - e0 + 1))
+                src, psrc = np.ascontiguousarray(v2[e0:e0 + cnt]), np.ascontiguousarray(p2[e0:e0 + cnt])
+                if rng.random() < 0.5:
+                    batch.upload_worlds(torch.from_numpy(src).cuda(), torch.from_numpy(psrc).cuda() if new_pal else None,
+                                        first_env=e0, stream=_stream())
+                else:
+                    batch.upload_worlds(src, psrc if new_pal else None, first_env=e0, stream=_stream())
+                v2 = cur_v.copy()
+                v2[e0:e0 + cnt] = src
+                if new_pal:
+                    p2, keep = cur_p.copy(), p2
+                    p2[e0:e0 + cnt] = keep[e0:e0 + cnt]
+            cur_v = v2
+            if new_pal:
+                cur_p = p2
+            ob.upload_worlds(cur_v, cur_p)
+            c2 = synth.random_cameras(rng, N * A, grid, margin=float(rng.choice([0.0, 0.5])))
+            batch.set_cameras(torch.from_numpy(c2).cuda(), stream=_stream())
+            ob.set_cameras(c2)
+            torch.cuda.synchronize()
+            run.render()
+            _pixelwise_rule(run.numpy(), ob.render(), where)
+        batch.close()
+        ob.close()
+
+
 def test_worlds_taller_than_the_staged_layers(lib, orc):
     """The render keeps only the lowest layers of a grid on chip (as many as the tallest world it has heard of
     needs).  With that number forced below what the worlds need, every workgroup traces through device
