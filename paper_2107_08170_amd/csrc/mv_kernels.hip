@@ -462,7 +462,9 @@ __global__ void update_voxels_kernel(const int32_t* __restrict__ env, const int3
     if (kFill) {
         atomicOr(xrow, 1ull << (i & 63));
         atomicOr(yrow, 1ull << (j & 63));
-        if (atomicMax(ztop + n, k + 1) < k + 1) report_height(heights, k + 1);
+        // (the bound only grows while edits are applied, and hardly any edit raises it: look before the atomic)
+        if (__hip_atomic_load(ztop + n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < k + 1)
+            if (atomicMax(ztop + n, k + 1) < k + 1) report_height(heights, k + 1);
     } else {
         atomicAnd(xrow, ~(1ull << (i & 63)));
         atomicAnd(yrow, ~(1ull << (j & 63)));
