@@ -1335,6 +1335,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const int last_material = p.materials_plus_one - 1;
 
     // a6 + a7 of a finished tile: material -> colour, then the stores.
+    // (PACKED launches without auxiliary outputs: `pix` is the wave-uniform pixel offset of the tile, and the two
+    // store offsets are a per-lane constant plus a scalar multiple of it)
+    const uint32_t lane_depth_off = 4u * (uint32_t)lane_pix, lane_rgb_off = 3u * (uint32_t)lane_pix + (uint32_t)quad;
     auto shade_and_store = [&](int idx, int hit_face, float t, int material, uint32_t pix, bool active, auto trusted_face) {
         // branch-free: lanes that found nothing look up a valid entry as well and then take the miss values
         const bool hit = idx >= 0;
@@ -1345,7 +1348,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         const float depth = hit ? t : 0.0f;
         const int face = hit ? hit_face : 255;
         material = hit ? material : 0;
-        if (active) {
+        if (PACKED && !AUX) {
+            *reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(depth_obs) + (lane_depth_off + 4u * pix)) = depth;
+        } else if (active) {
             depth_obs[pix] = depth;
             if (AUX) {
                 if (auxm_obs) auxm_obs[pix] = (uint8_t)material;
@@ -1359,8 +1364,10 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             // worth of pixel m and the lower m+1 bytes of pixel m+1.
             const uint32_t next = next_in_quad(colour);
             const uint32_t word = (colour >> (8 * quad)) | (next << (24 - 8 * quad));
-            if (quad < 3)
-                *reinterpret_cast<uint32_t*>(rgb_obs + (3u * pix + (uint32_t)quad)) = word;
+            if (quad < 3) {
+                if (!AUX) *reinterpret_cast<uint32_t*>(rgb_obs + (lane_rgb_off + 3u * pix)) = word;
+                else *reinterpret_cast<uint32_t*>(rgb_obs + (3u * pix + (uint32_t)quad)) = word;
+            }
         } else if (active) {
             uint8_t* out = rgb_obs + 3u * pix;
             out[0] = (uint8_t)colour;
@@ -1399,7 +1406,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             if (PACKED) {
                 sx = sx_lane[tx * kTileW];
                 rr = rowrec_lane[ty * kTileH];
-                pix = (uint32_t)(lane_pix + ty * kTileH * p.W + tx * kTileW);
+                pix = AUX ? (uint32_t)(lane_pix + ty * kTileH * p.W + tx * kTileW) : (uint32_t)(ty * kTileH * p.W + tx * kTileW);
             } else {
                 const int col = tx * kTileW + lx, row = ty * kTileH + ly;
                 active = col < p.W && row < p.H;
